@@ -1,0 +1,73 @@
+"""Glue shared by the tests: turn a workload configuration into oracle inputs."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import workload as wl
+
+
+def oracle_model(cfg: wl.RankingConfig, bf16_gemm=None) -> oracle.Model:
+    return oracle.Model(cfg.num_fields, cfg.rows_per_field, cfg.dim, cfg.num_dense,
+                        tuple(cfg.layer_sizes), cfg.adagrad_state == "rowwise",
+                        cfg.table_dtype == "bf16",
+                        (cfg.gemm_dtype == "bf16") if bf16_gemm is None else bf16_gemm,
+                        cfg.lr, cfg.eps)
+
+
+def tables_as_f32(cfg, tables):
+    """[F*R, D] stored tables -> float32 values."""
+    return tables if cfg.table_dtype == "f32" else wl.bf16_bits_to_f32(tables)
+
+
+def per_field(cfg, arr):
+    R = cfg.rows_per_field
+    return [arr[f * R:(f + 1) * R] for f in range(cfg.num_fields)]
+
+
+def oracle_iteration(cfg, tables_f32, state, flat_params, flat_state, batch, sizes,
+                     mask=None, bf16_gemm=None, want_samples=False):
+    """Run worker_step for every shard, aggregate and apply_update with the oracle."""
+    model = oracle_model(cfg, bf16_gemm)
+    tabs = per_field(cfg, tables_f32)
+    st = per_field(cfg, state)
+    layers = wl.split_params(cfg, flat_params)
+    lstate = wl.split_params(cfg, flat_state)
+    res = [oracle.worker_step(model, tabs, layers, batch, s, n) for s, n in wl.shard_slices(sizes)]
+    agg = oracle.aggregate(model, batch, res, mask, want_samples)
+    upd = oracle.apply_update(model, tabs, st, layers, lstate, agg)
+    return model, res, agg, upd
+
+
+def flat_dense_grad(cfg, dW, db):
+    out = np.zeros(cfg.num_params, dtype=np.float64)
+    for (wo, bo, fi, fo), W, b in zip(wl.param_layout(cfg), dW, db):
+        out[wo:bo] = np.asarray(W).reshape(-1)
+        out[bo:bo + fo] = np.asarray(b).reshape(-1)
+    return out
+
+
+def flat_layers(cfg, layers):
+    return flat_dense_grad(cfg, [W for W, _ in layers], [b for _, b in layers])
+
+
+def rel_err(a, b):
+    """(normwise, maxwise) relative error of a against the reference b."""
+    a = np.asarray(a, dtype=np.float64).reshape(-1)
+    b = np.asarray(b, dtype=np.float64).reshape(-1)
+    if b.size == 0:
+        return 0.0, 0.0
+    nb = max(float(np.linalg.norm(b)), 1e-300)
+    mb = max(float(np.max(np.abs(b))), 1e-300)
+    return float(np.linalg.norm(a - b)) / nb, float(np.max(np.abs(a - b))) / mb
+
+
+def assert_close(a, b, tol, what=""):
+    n, m = rel_err(a, b)
+    assert n <= tol and m <= tol, f"{what}: normwise {n:.3e}, maxwise {m:.3e} > {tol:.1e}"
+
+
+TINY = wl.RankingConfig("tiny", 2, 7, 3, "f32", "elementwise", 2, (8, 4, 1), "f32", 3, 1.05,
+                        (2, 3), wl.SEED0 + 101, min_bag=0)
+SMALL = wl.RankingConfig("small", 3, 50, 4, "f32", "elementwise", 3, (15, 8, 6, 1), "f32", 4, 1.05,
+                         (5, 1, 0, 6), wl.SEED0 + 102, min_bag=0)

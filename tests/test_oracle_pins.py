@@ -1,0 +1,437 @@
+"""Pins of the CPU oracle against things other than itself (all CPU, no GPU).
+
+Library special cases (torch-CPU embedding_bag / autograd / Adagrad / Adam),
+finite differences, closed forms, invariants of the data-parallel setting
+(Section II: fixed global batch, sum_i B_i = B) and brute force on tiny inputs.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workload as wl
+from helpers import (SMALL, TINY, assert_close, flat_dense_grad, flat_layers, oracle_iteration,
+                     oracle_model, per_field, rel_err)
+
+
+# ---------------------------------------------------------------- torch twin
+def torch_iteration(cfg, tables, flat_params, batch, steps=1, lr=None, eps=None):
+    """Whole-batch training step(s) with torch-CPU float64 library ops only."""
+    lr = cfg.lr if lr is None else lr
+    eps = cfg.eps if eps is None else eps
+    F, R, D = cfg.num_fields, cfg.rows_per_field, cfg.dim
+    tabs = [torch.tensor(tables[f * R:(f + 1) * R], dtype=torch.float64, requires_grad=True)
+            for f in range(F)]
+    layers = [(torch.tensor(W, dtype=torch.float64, requires_grad=True),
+               torch.tensor(b, dtype=torch.float64, requires_grad=True))
+              for W, b in wl.split_params(cfg, flat_params)]
+    params = tabs + [t for Wb in layers for t in Wb]
+    opt = torch.optim.Adagrad(params, lr=lr, eps=eps, initial_accumulator_value=0.0)
+    out = None
+    for _ in range(steps):
+        opt.zero_grad()
+        cols = []
+        for f in range(F):
+            ids = torch.tensor(batch.field_ids(f), dtype=torch.int64)
+            off = torch.tensor(batch.offsets[f][:-1], dtype=torch.int64)
+            cols.append(torch.nn.functional.embedding_bag(ids, tabs[f], off, mode="sum"))
+        x = torch.cat(cols + [torch.tensor(batch.dense, dtype=torch.float64)], dim=1)
+        h = x
+        for l, (W, b) in enumerate(layers):
+            h = h @ W + b
+            if l < len(layers) - 1:
+                h = torch.relu(h)
+        z = h[:, 0]
+        loss = torch.nn.functional.binary_cross_entropy_with_logits(
+            z, torch.tensor(batch.labels, dtype=torch.float64), reduction="mean")
+        loss.backward()
+        if out is None:
+            out = dict(x=x.detach().numpy().copy(), z=z.detach().numpy().copy(), loss=float(loss.detach()),
+                       table_grads=[t.grad.numpy().copy() for t in tabs],
+                       dW=[W.grad.numpy().copy() for W, _ in layers],
+                       db=[b.grad.numpy().copy() for _, b in layers])
+        opt.step()
+    out["tables"] = [t.detach().numpy() for t in tabs]
+    out["layers"] = [(W.detach().numpy(), b.detach().numpy()) for W, b in layers]
+    return out
+
+
+def fresh(cfg, batch_index=0, batch=None):
+    tables = wl.make_tables(cfg)
+    flat = wl.make_mlp_params(cfg)
+    b = wl.make_batch(cfg, batch_index, batch)
+    state = np.zeros_like(tables, dtype=np.float32) if cfg.adagrad_state == "elementwise" \
+        else np.zeros(tables.shape[0], np.float32)
+    return tables, state, flat, np.zeros_like(flat), b
+
+
+@pytest.mark.parametrize("cfg", [wl.CONFIGS[1], SMALL], ids=lambda c: c.name)
+def test_iteration_matches_torch_whole_batch(cfg):
+    """Forward, loss, aggregated gradients and the Adagrad update of a K-shard
+    iteration equal torch's whole-batch step (library special case + invariance
+    to the split)."""
+    tables, state, flat, fstate, batch = fresh(cfg)
+    ref = torch_iteration(cfg, tables, flat, batch)
+    model, res, agg, upd = oracle_iteration(cfg, tables, state, flat, fstate, batch, cfg.shard_sizes)
+    x = np.concatenate([r.x for r in res])
+    z = np.concatenate([r.z for r in res])
+    assert_close(x, ref["x"], 1e-12, "pooled input")
+    assert_close(z, ref["z"], 1e-12, "logits")
+    assert abs(agg.loss - ref["loss"]) <= 1e-12 * abs(ref["loss"])
+    for l in range(len(agg.dW)):
+        assert_close(agg.dW[l], ref["dW"][l], 1e-11, f"dW{l}")
+        assert_close(agg.db[l], ref["db"][l], 1e-11, f"db{l}")
+    R = cfg.rows_per_field
+    for f in range(cfg.num_fields):
+        dense_g = np.zeros((R, cfg.dim))
+        dense_g[agg.unique_ids[f]] = agg.G[f]
+        assert_close(dense_g, ref["table_grads"][f], 1e-11, f"table grad {f}")
+        new = np.asarray(tables[f * R:(f + 1) * R], dtype=np.float64).copy()
+        new[agg.unique_ids[f]] = upd.rows[f]
+        # stored rows are rounded to float32 once
+        assert_close(new, ref["tables"][f].astype(np.float32), 1e-12, f"updated table {f}")
+        assert_close(new - tables[f * R:(f + 1) * R], ref["tables"][f] - tables[f * R:(f + 1) * R],
+                     1e-5, f"table delta {f}")
+    for l, (W, b) in enumerate(upd.layers):
+        assert_close(W, ref["layers"][l][0].astype(np.float32), 1e-12, f"W{l}")
+        assert_close(b, ref["layers"][l][1].astype(np.float32), 1e-12, f"b{l}")
+
+
+def test_two_steps_match_torch_adagrad_state():
+    """Second step runs from a non-zero accumulator: S += g^2 carries over."""
+    cfg = SMALL
+    tables, state, flat, fstate, batch = fresh(cfg)
+    ref = torch_iteration(cfg, tables, flat, batch, steps=2)
+    t64 = tables.astype(np.float64)
+    s64 = state.astype(np.float64)
+    p64, ps64 = flat.astype(np.float64), fstate.astype(np.float64)
+    R = cfg.rows_per_field
+    for _ in range(2):
+        model = oracle_model(cfg)
+        layers = wl.split_params(cfg, p64)
+        lstate = wl.split_params(cfg, ps64)
+        res = [oracle.worker_step(model, per_field(cfg, t64), layers, batch, s, n)
+               for s, n in wl.shard_slices(cfg.shard_sizes)]
+        agg = oracle.aggregate(model, batch, res)
+        for f in range(cfg.num_fields):   # unrounded update, to follow torch's float64 exactly
+            u = agg.unique_ids[f]
+            p1, s1 = oracle.adagrad_elementwise(t64[f * R + u], s64[f * R + u], agg.G[f], cfg.lr, cfg.eps)
+            t64[f * R + u], s64[f * R + u] = p1, s1
+        g = flat_dense_grad(cfg, agg.dW, agg.db)
+        p64, ps64 = oracle.adagrad_elementwise(p64, ps64, g, cfg.lr, cfg.eps)
+    for f in range(cfg.num_fields):
+        assert_close(t64[f * R:(f + 1) * R], ref["tables"][f], 1e-12, f"table {f} after 2 steps")
+    assert_close(p64, flat_layers(cfg, ref["layers"]), 1e-12, "dense params after 2 steps")
+
+
+# ------------------------------------------------------ finite differences
+def whole_batch_loss(cfg, tables64, flat64, batch):
+    model = oracle_model(cfg)
+    r = oracle.worker_step(model, per_field(cfg, tables64), wl.split_params(cfg, flat64), batch, 0,
+                           batch.batch)
+    return r.loss, r
+
+
+def test_finite_differences_tiny():
+    cfg = TINY
+    tables, state, flat, fstate, batch = fresh(cfg)
+    tables64, flat64 = tables.astype(np.float64), flat.astype(np.float64) * 3.0
+    # keep every pre-activation away from the ReLU kink
+    _, r = whole_batch_loss(cfg, tables64, flat64, batch)
+    pre = r.acts[1]
+    assert np.all((pre == 0) | (pre > 1e-3))
+    model = oracle_model(cfg)
+    res = [oracle.worker_step(model, per_field(cfg, tables64), wl.split_params(cfg, flat64), batch, s, n)
+           for s, n in wl.shard_slices(cfg.shard_sizes)]
+    agg = oracle.aggregate(model, batch, res)
+    g = flat_dense_grad(cfg, agg.dW, agg.db)
+    h = 1e-6
+    fd = np.zeros_like(g)
+    for i in range(cfg.num_params):
+        p = flat64.copy(); p[i] += h
+        m = flat64.copy(); m[i] -= h
+        fd[i] = (whole_batch_loss(cfg, tables64, p, batch)[0] -
+                 whole_batch_loss(cfg, tables64, m, batch)[0]) / (2 * h)
+    assert_close(g, fd, 1e-6, "dense gradient vs central differences")
+    R, D = cfg.rows_per_field, cfg.dim
+    for f in range(cfg.num_fields):
+        dense_g = np.zeros((R, D))
+        dense_g[agg.unique_ids[f]] = agg.G[f]
+        fdt = np.zeros((R, D))
+        for r_ in range(R):
+            for d in range(D):
+                p = tables64.copy(); p[f * R + r_, d] += h
+                m = tables64.copy(); m[f * R + r_, d] -= h
+                fdt[r_, d] = (whole_batch_loss(cfg, p, flat64, batch)[0] -
+                              whole_batch_loss(cfg, m, flat64, batch)[0]) / (2 * h)
+        assert_close(dense_g, fdt, 1e-6, f"table gradient {f} vs central differences")
+        untouched = np.setdiff1d(np.arange(R), agg.unique_ids[f])
+        assert np.all(fdt[untouched] == 0.0)
+
+
+# ------------------------------------------------ invariance to the split
+@pytest.mark.parametrize("sizes", [(12,), (3, 9), (5, 1, 0, 6), (1,) * 12, (0, 12, 0)])
+def test_partition_invariance(sizes):
+    """sum_k (B_k/B) g_k is the whole-batch gradient whatever the split (fixed global batch)."""
+    cfg = SMALL
+    tables, state, flat, fstate, batch = fresh(cfg)
+    _, _, ref, uref = oracle_iteration(cfg, tables, state, flat, fstate, batch, (12,))
+    _, res, agg, upd = oracle_iteration(cfg, tables, state, flat, fstate, batch, sizes)
+    assert abs(agg.loss - ref.loss) < 1e-12
+    for l in range(len(ref.dW)):
+        assert_close(agg.dW[l], ref.dW[l], 1e-12)
+        assert_close(agg.db[l], ref.db[l], 1e-12)
+    for f in range(cfg.num_fields):
+        assert np.array_equal(agg.unique_ids[f], ref.unique_ids[f])
+        assert np.array_equal(agg.seg_offsets[f], ref.seg_offsets[f])
+        assert_close(agg.G[f], ref.G[f], 1e-12)
+        assert np.array_equal(upd.rows[f], uref.rows[f]) or rel_err(upd.rows[f], uref.rows[f])[0] < 1e-7
+
+
+def test_row_sparsity_and_touched_rows_move():
+    cfg = SMALL
+    tables, state, flat, fstate, batch = fresh(cfg)
+    _, res, agg, upd = oracle_iteration(cfg, tables, state, flat, fstate, batch, cfg.shard_sizes)
+    R = cfg.rows_per_field
+    for f in range(cfg.num_fields):
+        present = np.unique(batch.field_ids(f))
+        assert np.array_equal(agg.unique_ids[f], present)
+        assert len(upd.rows[f]) == len(present)
+        g_nonzero = np.abs(agg.G[f]) > 0
+        moved = upd.rows[f] != tables[f * R + present]
+        assert np.array_equal(moved, g_nonzero)
+        # first Adagrad step from S = 0: |delta| = lr*|g|/(|g|+eps) ~ lr wherever g != 0
+        delta = upd.rows[f] - tables[f * R + present]
+        assert np.allclose(np.abs(delta[g_nonzero]), cfg.lr, rtol=1e-3)
+        assert np.array_equal(np.sign(delta[g_nonzero]), -np.sign(agg.G[f][g_nonzero]))
+
+
+def test_masked_shards_are_excluded_and_weights_renormalise():
+    cfg = SMALL
+    tables, state, flat, fstate, batch = fresh(cfg)
+    sizes = (4, 3, 5)
+    model, res, agg_all, _ = oracle_iteration(cfg, tables, state, flat, fstate, batch, sizes)
+    agg = oracle.aggregate(model, batch, res, mask=[True, False, True])
+    assert np.allclose(agg.weights, [4 / 9, 0, 5 / 9])
+    for f in range(cfg.num_fields):
+        off = batch.offsets[f]
+        kept = np.concatenate([batch.field_ids(f)[off[0]:off[4]], batch.field_ids(f)[off[7]:off[12]]])
+        assert np.array_equal(agg.unique_ids[f], np.unique(kept))
+        assert agg.seg_offsets[f][-1] == len(kept)
+    assert_close(agg.dW[0], (4 * res[0].dW[0] + 5 * res[2].dW[0]) / 9, 1e-14)
+
+
+# --------------------------------------------------------------- coalescing
+@pytest.mark.parametrize("case", ["random", "all_equal", "all_distinct", "sorted", "reverse", "max_id",
+                                  "empty"])
+def test_coalescing_against_dictionary(case):
+    rng = np.random.default_rng(7)
+    R, D, B = 40, 3, 30
+    if case == "random":
+        bags = [[list(rng.integers(0, R, rng.integers(0, 5))) for _ in range(B)]]
+    elif case == "all_equal":
+        bags = [[[17, 17] for _ in range(B)]]
+    elif case == "all_distinct":
+        bags = [[[s] for s in range(B)]]
+    elif case == "sorted":
+        bags = [[[s, s + 1] for s in range(B)]]
+    elif case == "reverse":
+        bags = [[[R - 1 - s] for s in range(B)]]
+    elif case == "max_id":
+        bags = [[[R - 1] if s % 2 else [0, R - 1] for s in range(B)]]
+    else:
+        bags = [[[] for _ in range(B)]]
+    batch = wl.batch_from_bags(bags, np.zeros((B, 0)), np.zeros(B))
+    model = oracle.Model(1, R, D, 0, (D, 1))
+    dx = rng.standard_normal((B, D))
+    sizes = (7, 0, 13, 10)
+    res = [oracle.ShardResult(s, n, None, None, 0.0, [np.zeros((D, 1))], [np.zeros(1)], dx[s:s + n])
+           for s, n in wl.shard_slices(sizes)]
+    agg = oracle.aggregate(model, batch, res, want_samples=True)
+    w = np.repeat(np.array(sizes) / B, sizes)
+    ids = batch.field_ids(0)
+    sample = np.repeat(np.arange(B), np.diff(batch.offsets[0]))
+    keys, seg, G = oracle.coalesce_loops(ids, (w[:, None] * dx)[sample])
+    assert np.array_equal(agg.unique_ids[0], keys)
+    assert np.array_equal(agg.seg_offsets[0], seg)
+    assert_close(agg.G[0], G, 1e-13)
+    # structure: ascending ids, offsets start at 0, strictly increase, end at nnz
+    assert np.all(np.diff(agg.unique_ids[0]) > 0)
+    assert agg.seg_offsets[0][0] == 0 and agg.seg_offsets[0][-1] == len(ids)
+    assert np.all(np.diff(agg.seg_offsets[0]) > 0)
+    # conservation: column sums of G equal column sums over all lookups
+    assert np.allclose(agg.G[0].sum(axis=0) if len(keys) else np.zeros(D),
+                       (w[:, None] * dx)[sample].sum(axis=0), atol=1e-12)
+    for u, k in enumerate(keys):
+        assert agg.seg_samples[0][u] == sorted(int(s) for s in sample[ids == k])
+
+
+def test_pool_loops_and_torch_embedding_bag():
+    rng = np.random.default_rng(3)
+    R, D, B = 11, 5, 9
+    table = rng.standard_normal((R, D)).astype(np.float32)
+    bags = [[list(rng.integers(0, R, rng.integers(0, 4))) for _ in range(B)]]
+    bags[0][2] = [4, 4, 4]          # duplicates count every time
+    batch = wl.batch_from_bags(bags, np.zeros((B, 0)), np.zeros(B))
+    a = oracle.embedding_pool(table, batch.field_ids(0), batch.offsets[0], 2, 6)
+    b = oracle.embedding_pool_loops(table, batch.field_ids(0), batch.offsets[0], 2, 6)
+    assert np.array_equal(a, b)
+    t = torch.nn.functional.embedding_bag(torch.tensor(batch.field_ids(0), dtype=torch.int64),
+                                          torch.tensor(table, dtype=torch.float64),
+                                          torch.tensor(batch.offsets[0][:-1], dtype=torch.int64),
+                                          mode="sum").numpy()
+    assert_close(a, t[2:8], 1e-14)
+    assert np.array_equal(a[0], 3.0 * table[4].astype(np.float64))
+
+
+# ------------------------------------------------------------------ loss
+def test_loss_closed_forms_and_weighted_mean():
+    assert abs(oracle.bce_with_logits(np.zeros(1), np.ones(1))[0] - math.log(2.0)) < 1e-15
+    z = np.array([-800.0, 800.0, 3.0])
+    y = np.array([1.0, 1.0, 0.0])
+    l = oracle.bce_with_logits(z, y)
+    assert l[0] == 800.0 and l[1] == 0.0 and abs(l[2] - math.log1p(math.exp(3.0))) < 1e-14
+    cfg = SMALL
+    tables, state, flat, fstate, batch = fresh(cfg)
+    _, res, agg, _ = oracle_iteration(cfg, tables, state, flat, fstate, batch, cfg.shard_sizes)
+    whole, _ = whole_batch_loss(cfg, tables.astype(np.float64), flat.astype(np.float64), batch)
+    assert abs(agg.loss - whole) < 1e-13
+
+
+# --------------------------------------------------------------- optimizers
+def test_adagrad_closed_forms():
+    g = np.array([[0.3, -2.0, 1e-6, 0.0]])
+    p = np.array([[1.0, 1.0, 1.0, 1.0]])
+    p1, s1 = oracle.adagrad_elementwise(p, np.zeros_like(p), g, 0.01, 1e-8)
+    assert np.allclose(p1 - p, -0.01 * g / (np.abs(g) + 1e-8), rtol=0, atol=1e-15)
+    assert p1[0, 3] == 1.0 and s1[0, 3] == 0.0          # g = 0, S = 0: exactly no change
+    # constant gradient for t steps: p_t = p_0 - lr * sum_i g / (sqrt(i)*|g| + eps)
+    pt, st = p.copy(), np.zeros_like(p)
+    for _ in range(5):
+        pt, st = oracle.adagrad_elementwise(pt, st, g, 0.01, 1e-8)
+    want = p - 0.01 * sum(g / (math.sqrt(i) * np.abs(g) + 1e-8) for i in range(1, 6))
+    assert np.allclose(pt, want, rtol=0, atol=1e-15)
+    # one column: the row-wise rule is the element-wise rule
+    g1 = np.array([[0.5], [-0.25], [0.0]])
+    a = oracle.adagrad_elementwise(np.ones((3, 1)), np.full((3, 1), 0.2), g1, 0.01, 1e-8)
+    b = oracle.adagrad_rowwise(np.ones((3, 1)), np.full(3, 0.2), g1, 0.01, 1e-8)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1][:, 0], b[1])
+    # row-wise accumulator is the mean of squares over the row, shared by all its columns
+    gg = np.array([[3.0, 4.0]])
+    pr, sr = oracle.adagrad_rowwise(np.zeros((1, 2)), np.zeros(1), gg, 1.0, 0.0)
+    assert sr[0] == 12.5 and np.allclose(pr, -gg / math.sqrt(12.5))
+
+
+def test_rowwise_update_in_iteration():
+    cfg = wl.scaled(SMALL, adagrad_state="rowwise")
+    tables, state, flat, fstate, batch = fresh(cfg)
+    state = state + np.float32(0.5)
+    _, res, agg, upd = oracle_iteration(cfg, tables, state, flat, fstate, batch, cfg.shard_sizes)
+    R = cfg.rows_per_field
+    for f in range(cfg.num_fields):
+        u = agg.unique_ids[f]
+        s1 = 0.5 + (agg.G[f] ** 2).mean(axis=1)
+        assert_close(upd.row_state[f], s1.astype(np.float32), 1e-12)
+        want = tables[f * R + u] - cfg.lr * agg.G[f] / (np.sqrt(s1)[:, None] + cfg.eps)
+        assert_close(upd.rows[f], want.astype(np.float32), 1e-12)
+
+
+def test_adam_against_torch_and_closed_forms():
+    dc = wl.DENSE_CONFIG
+    n = 10_000
+    p, m, v, grads, w = wl.make_dense_problem(dc, n, weights=np.array([512, 768, 1024, 1536, 2048, 2560,
+                                                                      3072, 4096]) / 15616)
+    tp = torch.tensor(p, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([tp], lr=dc.lr, betas=(dc.beta1, dc.beta2), eps=dc.eps)
+    p64, m64, v64 = p.astype(np.float64), m.astype(np.float64), v.astype(np.float64)
+    for step in range(1, 4):
+        gs = [g * (1.0 + 0.1 * step) for g in grads]
+        gbar = sum(float(wk) * gk.astype(np.float64) for wk, gk in zip(w, gs))
+        tp.grad = torch.tensor(gbar)
+        opt.step()
+        p64, m64, v64 = oracle.dense_aggregate_adam(p64, m64, v64, gs, w, dc.lr, dc.beta1, dc.beta2,
+                                                    dc.eps, step)
+        assert_close(p64, tp.detach().numpy(), 1e-12, f"adam step {step}")
+    # first step from m = v = 0: delta = -lr * g/(|g| + eps)  ~  -lr * sign(g)
+    g = oracle.weighted_average(grads, w)
+    p1, m1, v1 = oracle.adam_step(p, 0 * p, 0 * p, g, dc.lr, dc.beta1, dc.beta2, dc.eps, 1)
+    assert np.allclose(p1 - p, -dc.lr * g / (np.abs(g) + dc.eps), rtol=1e-9, atol=0)
+    # one-hot weights pick a buffer, equal weights give the arithmetic mean
+    e3 = np.eye(8)[3]
+    assert np.array_equal(oracle.weighted_average(grads, e3), grads[3].astype(np.float64))
+    assert_close(oracle.weighted_average(grads, np.full(8, 0.125)),
+                 np.mean(np.stack(grads).astype(np.float64), axis=0), 1e-15)
+
+
+# --------------------------------------------------------------- bf16
+def test_round_bf16_ties_and_library():
+    one = 1.0
+    ulp = 2.0 ** -7                       # spacing of bf16 in [1, 2)
+    assert oracle.round_bf16(one + ulp / 2) == 1.0               # tie -> even mantissa (1.0)
+    assert oracle.round_bf16(one + ulp + ulp / 2) == one + 2 * ulp  # tie -> even (up)
+    assert oracle.round_bf16(one + ulp / 2 + 2.0 ** -20) == one + ulp
+    assert oracle.round_bf16(-(one + ulp / 2)) == -1.0
+    x = np.random.default_rng(0).standard_normal(20000).astype(np.float32) * 3
+    lib = torch.tensor(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(oracle.round_bf16(x), lib)
+    # widening is exact: a bf16 value survives the round trip
+    assert np.array_equal(oracle.round_bf16(lib), lib)
+    assert np.array_equal(wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x)).astype(np.float64), lib)
+
+
+def test_bf16_gemm_mode_is_exact_on_bf16_representable_integers():
+    """With small-integer operands every product and sum is exact, so the bf16-operand
+    mode and the plain mode agree bit for bit; with generic operands they differ by the
+    bf16 rounding of the operands only (well below 2e-2)."""
+    rng = np.random.default_rng(5)
+    x = rng.integers(-3, 4, (6, 5)).astype(np.float64)
+    layers = [(rng.integers(-2, 3, (5, 4)).astype(np.float64), rng.integers(-2, 3, 4).astype(np.float64)),
+              (rng.integers(-2, 3, (4, 1)).astype(np.float64), np.zeros(1))]
+    a0, z0 = oracle.mlp_forward(x, layers, False)
+    a1, z1 = oracle.mlp_forward(x, layers, True)
+    assert np.array_equal(z0, z1) and all(np.array_equal(p, q) for p, q in zip(a0, a1))
+    cfg = SMALL
+    tables, state, flat, fstate, batch = fresh(cfg)
+    _, _, agg0, _ = oracle_iteration(cfg, tables, state, flat, fstate, batch, cfg.shard_sizes, bf16_gemm=False)
+    _, _, agg1, _ = oracle_iteration(cfg, tables, state, flat, fstate, batch, cfg.shard_sizes, bf16_gemm=True)
+    n, _ = rel_err(agg1.dW[0], agg0.dW[0])
+    assert 0 < n < 2e-2
+
+
+# ------------------------------------------------------- shard assignment
+def test_eq3_bruteforce_properties():
+    from fractions import Fraction
+    for speeds, B in [((1.0, 1.0, 1.0), 9), ((1.0, 2.0, 4.0), 14), ((3.0, 1.0), 16), ((0.5, 1.5, 1.0, 2.0), 10)]:
+        z, arg = oracle.minmax_split_bruteforce(B, speeds)
+        # the continuous relaxation B_i = B v_i / sum v bounds the integer optimum from below
+        assert z >= Fraction(B) / sum(Fraction(v) for v in speeds)
+        for a in arg:
+            assert sum(a) == B and oracle.minmax_objective(a, speeds) == z
+    z, arg = oracle.minmax_split_bruteforce(9, (1.0, 1.0, 1.0))
+    assert arg == [(3, 3, 3)] and z == 3                       # equal speeds -> B/n each
+    z, arg = oracle.minmax_split_bruteforce(14, (1.0, 2.0, 4.0))
+    assert (2, 4, 8) in arg and z == 2                         # speeds divide B: exactly proportional
+    assert [n for _, n in oracle.equal_split(10, 4)] == [3, 3, 2, 2]
+    assert oracle.explicit_split((2, 0, 5)) == [(0, 2), (2, 0), (2, 5)]
+
+
+def test_data_shard_arithmetic():
+    N, B, M = 45_000_000, 81_920, 100          # the click-log run of Section VII-A
+    assert oracle.num_data_shards(N, B, M) == math.ceil(N / (B * M)) == 6
+    sh = oracle.data_shards(N, B, M)
+    assert sh[0] == (0, B * M) and sum(n for _, n in sh) == N
+    assert all(sh[i][0] + sh[i][1] == sh[i + 1][0] for i in range(len(sh) - 1))
+    assert oracle.data_shards(10, 2, 2) == [(0, 4), (4, 4), (8, 2)]
+
+
+def test_eq4_bruteforce():
+    # two device types, the second three times faster (cf. V100 vs P100 in Section I)
+    z, arg = oracle.accumulation_plan_bruteforce(32, (1, 1), (1.0, 3.0), (2, 2), (8, 8), 1, 3)
+    assert z is not None
+    for C, Bs in arg:
+        assert C[0] * Bs[0] + C[1] * Bs[1] == 32
+        assert max(C[0] * Bs[0] / 1.0, C[1] * Bs[1] / 3.0) == float(z)
+    assert float(z) == 8.0          # 8 samples on the slow type, 24 on the fast one
+    assert oracle.accumulation_plan_bruteforce(5, (2,), (1.0,), (1,), (2,), 1, 1)[0] is None
