@@ -1,0 +1,236 @@
+/*
+ * antdt.h — C boundary of the MI355X (gfx950) library for one bulk-synchronous
+ * Parameter-Server training iteration of a ranking model.
+ *
+ * The calls follow the iteration as the AntDT paper states it (Section II,
+ * Problem Formulation): given the fixed global batch B, worker i computes its
+ * local gradient on its local batch B_i and pushes it (antdt_worker_step); the
+ * servers aggregate the local gradients of all workers (antdt_aggregate) and
+ * update the parameters (antdt_apply_update).  Which samples a worker gets is a
+ * shard = (start offset, length) pair (Section V-C.1) produced by
+ * antdt_assign_shard; the lengths always add up to B (constraint of Eq. 1).
+ * On one device the K workers are K contiguous slices of the global batch and
+ * the pull/push communication of the paper's model has no counterpart.
+ *
+ * Conventions
+ *  - Every pointer marked DEVICE is device memory owned by the caller (for
+ *    example a torch tensor's data_ptr); HOST pointers are ordinary host memory
+ *    read or written before the call returns.  The library never allocates,
+ *    frees or retains device memory other than the buffers handed to
+ *    antdt_bind / antdt_set_batch, which must stay valid while in use.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    GPU calls enqueue their kernels on it and return without synchronising
+ *    unless stated otherwise.  Calls on one context must not overlap.
+ *  - Every function returns ANTDT_OK or a negative error code; a message is kept
+ *    per context (antdt_last_error).  Nothing throws, nothing aborts.
+ *  - Row ids outside [0, rows_per_field) and non-monotone bag offsets are caller
+ *    errors with undefined results.  An empty bag pools to zeros and receives
+ *    no gradient.  An empty shard (length 0) is legal and contributes nothing.
+ */
+#ifndef ANTDT_H_
+#define ANTDT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ANTDT_MAX_LAYERS 8
+#define ANTDT_MAX_FIELDS 128
+#define ANTDT_MAX_SHARDS 64
+
+enum {
+  ANTDT_OK = 0,
+  ANTDT_INVALID_ARG = -1,         /* null pointer, size out of range, sizes not summing to B ... */
+  ANTDT_BAD_STATE = -2,           /* call order violated (see each call) */
+  ANTDT_WORKSPACE_TOO_SMALL = -3,
+  ANTDT_HIP_ERROR = -4,           /* a HIP runtime call failed; message holds hipGetErrorString */
+  ANTDT_UNSUPPORTED = -5
+};
+
+enum { ANTDT_F32 = 0, ANTDT_BF16 = 1 };
+enum { ANTDT_STATE_ELEMENTWISE = 0, ANTDT_STATE_ROWWISE = 1 };
+
+typedef struct antdt_ctx antdt_ctx; /* opaque; holds host metadata only */
+
+/*
+ * Model descriptor (plain data, copied by antdt_create).
+ *
+ * Input vector of a sample = [pooled embedding of field 0 | ... | field F-1 |
+ * dense features], width layer_sizes[0] = num_fields*dim + num_dense.  The MLP
+ * has num_layers weight layers; hidden layers apply ReLU, the last layer is
+ * linear with a single output (layer_sizes[num_layers] == 1, the logit of a
+ * binary cross-entropy loss).
+ *
+ * Flat parameter layout (mlp_params, mlp_state, every dense gradient): for
+ * layer l = 0..num_layers-1, W_l as [layer_sizes[l], layer_sizes[l+1]]
+ * row-major, then b_l [layer_sizes[l+1]].
+ */
+typedef struct antdt_model {
+  int32_t num_fields;       /* F, 1..ANTDT_MAX_FIELDS */
+  int64_t rows_per_field;   /* R, < 2^31 */
+  int32_t dim;              /* D; D*sizeof(element) a power-of-two multiple of 16 bytes, <= 1024 B */
+  int32_t table_dtype;      /* ANTDT_F32 or ANTDT_BF16: element type of the embedding tables */
+  int32_t adagrad_state;    /* ELEMENTWISE: fp32 [F*R, D];  ROWWISE: fp32 [F*R] */
+  int32_t num_dense;        /* dense features per sample (may be 0) */
+  int32_t num_layers;       /* 1..ANTDT_MAX_LAYERS */
+  int32_t layer_sizes[ANTDT_MAX_LAYERS + 1];
+  int32_t gemm_dtype;       /* ANTDT_F32: fp32 FMA GEMMs.  ANTDT_BF16: hidden-layer GEMM operands
+                               are bf16, accumulation fp32 (matrix cores); hidden widths must then
+                               be multiples of 8 */
+  float lr;                 /* Adagrad learning rate (tables and MLP) */
+  float eps;                /* Adagrad epsilon, added to sqrt(state) */
+  int32_t max_shards;       /* K_max, 1..ANTDT_MAX_SHARDS */
+  int64_t max_batch;        /* largest global batch B */
+  int64_t max_nnz;          /* largest total number of lookups (all fields) of one batch */
+} antdt_model;
+
+/* Create / destroy a context.  Host work only.  INVALID_ARG on an inconsistent model. */
+int antdt_create(const antdt_model* model, antdt_ctx** out);
+int antdt_destroy(antdt_ctx* ctx);
+
+/* Message of the last failed call on ctx (ctx == NULL: of the last failed antdt_create or
+ * context-free call on this thread).  Never NULL. */
+const char* antdt_last_error(const antdt_ctx* ctx);
+
+/* Size in bytes of the scratch region antdt_bind needs (activations, per-shard gradients,
+ * sort buffers, coalesced gradients, bf16 weight copies). */
+int antdt_workspace_bytes(const antdt_ctx* ctx, size_t* bytes);
+
+/*
+ * Attach the caller's DEVICE buffers:
+ *   tables      [F*R, D]  table_dtype, field f occupies rows [f*R, (f+1)*R)
+ *   table_state fp32 [F*R, D] (element-wise) or [F*R] (row-wise)
+ *   mlp_params  fp32, flat layout above;  mlp_state fp32, same layout
+ *   workspace   256-byte aligned, >= antdt_workspace_bytes
+ * Enqueues the conversion of the MLP weights to their bf16 operand copies when
+ * gemm_dtype is BF16 (call again after changing mlp_params from outside).
+ */
+int antdt_bind(antdt_ctx* ctx, void* tables, float* table_state, float* mlp_params,
+               float* mlp_state, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Present one global batch of B samples (B <= max_batch) in CSR form per field:
+ *   ids       DEVICE int32 [field_ptr[F]]  lookups of field f at [field_ptr[f], field_ptr[f+1]),
+ *                                          bags in sample order
+ *   field_ptr HOST   int64 [F+1]           field_ptr[0] == 0, non-decreasing
+ *   offsets   DEVICE int32 [F][B+1]        bag s of field f = lookups [offsets[f][s], offsets[f][s+1])
+ *                                          relative to field_ptr[f]; offsets[f][B] == nnz_f
+ *   dense     DEVICE fp32  [B, num_dense]  (may be NULL when num_dense == 0)
+ *   labels    DEVICE fp32  [B]             0 or 1
+ * Only pointers and sizes are recorded; nothing is copied.  Resets the iteration state.
+ * Requires antdt_bind.
+ */
+int antdt_set_batch(antdt_ctx* ctx, const int32_t* ids, const int64_t* field_ptr,
+                    const int32_t* offsets, const float* dense, const float* labels,
+                    int64_t B, void* stream);
+
+/*
+ * Split the global batch into K contiguous shards (start, length), worker order, lengths
+ * summing to B (Section V-C.1; constraint of Eq. 1).  HOST work only.
+ *   sizes != NULL : explicit B_k (>= 0, must sum to B);
+ *   else speed != NULL : ADJUST_BS, Eq. 3 — integer B_k minimising max_k B_k / speed[k]
+ *                   (speed[k] > 0, samples per second); ties go to the lowest k;
+ *   else          : equal split B/K, the first B mod K shards one larger (Section VI-A, step 1).
+ * start_out / len_out: HOST int64 [K], may be NULL.  The split is stored in ctx for the
+ * following worker_step / aggregate calls.
+ */
+int antdt_assign_shard(antdt_ctx* ctx, int64_t B, int32_t K, const int64_t* sizes,
+                       const double* speed, int64_t* start_out, int64_t* len_out);
+
+/*
+ * Worker k's local step on its shard (Section II: forward and backpropagation on B_k):
+ * sum-pool the bags, MLP forward, mean binary cross-entropy over the shard, backward.
+ * Produces, inside the workspace, the pooled inputs, the shard's dense gradient (mean over
+ * the shard, flat layout) and d loss_k / d pooled-embedding for each of its samples — the
+ * pair (ids, that gradient) is the shard's sparse gradient.  loss_out: DEVICE fp32 [1], may
+ * be NULL.  Requires set_batch and assign_shard with matching B.
+ */
+int antdt_worker_step(antdt_ctx* ctx, int32_t k, float* loss_out, void* stream);
+
+/* The same for all K shards in one batched pass of launches; loss_out DEVICE fp32 [K] or NULL.
+ * Results per shard equal those of K antdt_worker_step calls. */
+int antdt_worker_step_all(antdt_ctx* ctx, float* loss_out, void* stream);
+
+/*
+ * Server-side aggregation of the pushed gradients (Section II: "the servers aggregate the
+ * local gradients from all workers") of the included shards, weights w_k = B_k / sum of the
+ * included B_k:
+ *   dense   g = sum_k w_k g_k;
+ *   sparse  per field: the lookups of the included shards are sorted by row id; the distinct
+ *           ids ascending (unique_ids), the start of each id's run (seg_offsets) and
+ *           G[u, :] = sum over the run of w_k(sample) * d loss_k / d pooled[sample, field].
+ * shard_mask: HOST uint8 [K], 0 = shard left out (its worker_step need not have run); NULL = all.
+ * Requires worker_step for every included shard since the last set_batch / apply_update.
+ */
+int antdt_aggregate(antdt_ctx* ctx, const uint8_t* shard_mask, void* stream);
+
+/*
+ * Parameter update (Section II: "update the parameters"): Adagrad with the aggregated
+ * gradient, S += g^2 (row-wise state: S[r] += mean_d g[r,d]^2), p -= lr * g / (sqrt(S) + eps),
+ * on the rows listed by the last aggregate only and on all MLP parameters; bf16 tables are
+ * written back round-to-nearest-even; bf16 operand copies of the MLP weights are refreshed.
+ * Requires antdt_aggregate.
+ */
+int antdt_apply_update(antdt_ctx* ctx, void* stream);
+
+/*
+ * Dense data-parallel step on one device (Section II: the AllReduce variant drops the
+ * server term): g = sum_k weights[k] * grads[k], then Adam with bias correction,
+ *   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
+ *   p -= lr * (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps),
+ * fused in one pass.  p, m, v: DEVICE fp32 [n], updated in place.  grads: HOST array of K
+ * DEVICE pointers to fp32 [n] (1 <= K <= 16).  weights: HOST fp32 [K].  step >= 1.
+ * All device pointers 16-byte aligned.  Context-free.
+ */
+int antdt_dense_aggregate_adam(float* p, float* m, float* v, const float* const* grads,
+                               const float* weights, int32_t K, int64_t n, float lr, float beta1,
+                               float beta2, float eps, int64_t step, void* stream);
+
+/*
+ * Fill embedding tables with their procedural initial values (input generation, not part
+ * of the iteration): value(f, r, d) = scale * (u * 2^-23 - 1), u = top 24 bits of
+ * fmix32(fmix32(r + 0x9E3779B9*(f+1)) ^ (0x85EBCA6B*(d+1))), fmix32 = MurmurHash3's 32-bit
+ * finaliser; rounded to nearest even when dtype is BF16.  tables: DEVICE [F*R, D].
+ */
+int antdt_fill_tables(void* tables, int32_t dtype, int32_t num_fields, int64_t rows_per_field,
+                      int32_t dim, float scale, void* stream);
+
+/*
+ * Read-only views into the workspace for checking results.  Pointers are DEVICE pointers,
+ * valid until the next call that recomputes them.  These calls synchronise `stream` where
+ * they need device-side counts.
+ */
+/* Pooled inputs of shard k: rows x ld elements of `dtype` (F32, or BF16 when gemm_dtype is
+ * BF16); columns [0, F*D + num_dense) are meaningful. */
+int antdt_view_pooled(antdt_ctx* ctx, int32_t k, const void** x, int64_t* rows, int64_t* ld,
+                      int32_t* dtype);
+/* Shard k's dense gradient (fp32, flat layout) and d loss_k / d pooled (fp32 [B_k, ld_dx]). */
+int antdt_view_shard_grads(antdt_ctx* ctx, int32_t k, const float** dense, const float** dx,
+                           int64_t* ld_dx);
+/* Aggregated dense gradient (fp32, flat layout). */
+int antdt_view_dense_grad(antdt_ctx* ctx, const float** g);
+/* Coalesced sparse gradient of field f after antdt_aggregate: unique_ids int32 [U_f] ascending,
+ * seg_offsets int32 [U_f + 1], seg_samples int32 [nnz_f] (global sample index of every sorted
+ * lookup; inside a run ascending), G fp32 [U_f, D].  Synchronises `stream`. */
+int antdt_view_coalesced(antdt_ctx* ctx, int32_t f, const int32_t** unique_ids,
+                         const int32_t** seg_offsets, const int32_t** seg_samples,
+                         int64_t* num_unique, int64_t* nnz, const float** G, void* stream);
+
+/*
+ * Optional per-kernel timing with HIP events on the launch stream.  mode 0: off;
+ * mode 1: every kernel class; mode 2: only the class `kernel_id`.  Timings accumulate until
+ * antdt_profile_read, which synchronises the recorded events and reports, per class, the
+ * number of launches and their total duration in milliseconds, then resets.
+ * antdt_kernel_name returns the class name (NULL past the last class).
+ */
+int antdt_profile(antdt_ctx* ctx, int32_t mode, int32_t kernel_id);
+int antdt_profile_read(antdt_ctx* ctx, int32_t kernel_id, int64_t* launches, double* total_ms);
+const char* antdt_kernel_name(int32_t kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANTDT_H_ */

@@ -1,0 +1,249 @@
+// Shared declarations of the gfx950 kernels and their host-side launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "antdt.h"
+
+namespace antdt {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// float -> bfloat16, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf2f(x); }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f2bf(x); }
+
+// Small tables passed to kernels by value (kernel-argument segment), so that no
+// host-to-device copy is needed per call.
+struct FieldPtr {
+  int64_t p[ANTDT_MAX_FIELDS + 1];  // start of each field's lookups inside ids
+};
+struct ShardTab {
+  int32_t K;
+  int32_t start[ANTDT_MAX_SHARDS];
+  int32_t len[ANTDT_MAX_SHARDS];
+  float w[ANTDT_MAX_SHARDS];  // aggregation weight B_k / sum of included B_k (0 if excluded)
+};
+struct TileBase {
+  int32_t t[ANTDT_MAX_FIELDS + 1];  // prefix sum of sort tiles per field
+};
+
+// Kernel classes for the optional event timing.
+enum KernelId {
+  KID_POOL = 0,
+  KID_GEMM_FWD,
+  KID_GEMM_DGRAD,
+  KID_GEMM_WGRAD,
+  KID_HEAD,
+  KID_HEAD_REDUCE,
+  KID_BIAS_GRAD,
+  KID_SORT_HIST,
+  KID_SORT_SCAN,
+  KID_SORT_SCATTER,
+  KID_SEG_HEADS,
+  KID_SEG_SCAN,
+  KID_SEG_EMIT,
+  KID_SEG_REDUCE,
+  KID_SEG_REDUCE_LONG,
+  KID_DENSE_AGG,
+  KID_SPARSE_ADAGRAD,
+  KID_DENSE_ADAGRAD,
+  KID_ADAM,
+  KID_COUNT
+};
+
+struct Profiler;  // defined in ctx.hip
+void prof_begin(Profiler* p, int kid, hipStream_t s);
+void prof_end(Profiler* p, int kid, hipStream_t s);
+
+struct ProfScope {
+  Profiler* p;
+  int kid;
+  hipStream_t s;
+  ProfScope(Profiler* p_, int kid_, hipStream_t s_) : p(p_), kid(kid_), s(s_) {
+    if (p) prof_begin(p, kid, s);
+  }
+  ~ProfScope() {
+    if (p) prof_end(p, kid, s);
+  }
+};
+
+// ---------------------------------------------------------------- embed.hip
+struct PoolArgs {
+  const void* tables;
+  const int32_t* ids;
+  const int32_t* offsets;
+  const float* dense;
+  void* x;
+  int32_t F, D, num_dense, ldx, B, s0, ns;
+  int64_t R;
+  int32_t table_bf16, x_bf16;
+};
+hipError_t launch_pool(const PoolArgs& a, const FieldPtr& fp, hipStream_t s);
+hipError_t launch_fill_tables(void* tables, int bf16, int F, int64_t R, int D, float scale,
+                              hipStream_t s);
+
+// ----------------------------------------------------------------- gemm.hip
+enum Epilogue { EPI_BIAS_RELU = 0, EPI_RELU_MASK = 1, EPI_PLAIN = 2 };
+
+// C[m, n] = sum_k A(m, k) * B(n, k).  a_kc: A(m,k) = A[m*lda + k], else A[k*lda + m];
+// b_kc: B(n,k) = B[n*ldb + k], else B[k*ldb + n].  With `grouped`, group g (blockIdx.z)
+// contracts over rows [tab.start[k0+g], +tab.len[k0+g]) of A and B (both not *_kc) and
+// writes C + (k0+g)*group_stride.
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  void* C;
+  const float* bias;   // EPI_BIAS_RELU: [N]
+  const void* mask;    // EPI_RELU_MASK: activations [M, ldmask], C = acc where mask > 0 else 0
+  int64_t lda, ldb, ldc, ldmask;
+  int32_t M, N, K;
+  int32_t a_kc, b_kc, epi;
+  int32_t bf16_in;     // operands (and mask) are bf16, else fp32
+  int32_t bf16_out;    // C is bf16, else fp32
+  int32_t grouped, k0, groups;
+  int64_t group_stride;
+};
+hipError_t launch_gemm(const GemmArgs& a, const ShardTab& tab, hipStream_t s);
+
+struct CastArgs {  // fp32 [rows, cols] -> bf16 [rows_pad, cols], extra rows zero
+  const float* src;
+  bf16_t* dst;
+  int64_t n_src, n_dst;
+};
+hipError_t launch_cast_bf16(const CastArgs& a, hipStream_t s);
+
+// ----------------------------------------------------------------- head.hip
+struct HeadArgs {
+  const void* h;        // [B, ldh] last hidden activation (or the pooled input when there is none)
+  const float* w;       // [width] last-layer weight
+  const float* b;       // [1]
+  const float* labels;  // [B]
+  float* z;             // [B]
+  float* loss_s;        // [B] per-sample loss
+  float* dz;            // [B] d(mean shard loss)/dz
+  void* dh;             // [B, lddh] gradient w.r.t. h (masked by h > 0 when `relu`), or fp32 dX
+  int64_t ldh, lddh;
+  int32_t width, dh_cols, relu, bf16_h, bf16_dh;
+  int32_t k_begin, k_end;
+};
+hipError_t launch_head(const HeadArgs& a, const ShardTab& tab, hipStream_t s);
+
+struct HeadReduceArgs {
+  const void* h;
+  const float* dz;
+  const float* loss_s;
+  float* grads;         // [K, P] per-shard flat dense gradients
+  float* loss_k;        // workspace [K]
+  float* loss_out;      // caller's buffer or NULL; element (k - k_begin)
+  int64_t ldh, P, w_off, b_off;
+  int32_t width, bf16_h, k_begin, k_end;
+};
+hipError_t launch_head_reduce(const HeadReduceArgs& a, const ShardTab& tab, hipStream_t s);
+
+struct BiasGradArgs {   // db[k][o] = sum over the shard's samples of dh[s, o]
+  const void* dh;
+  float* grads;
+  int64_t lddh, P, b_off;
+  int32_t width, bf16_dh, k_begin, k_end;
+};
+hipError_t launch_bias_grad(const BiasGradArgs& a, const ShardTab& tab, hipStream_t s);
+
+// ------------------------------------------------------------- coalesce.hip
+struct SortPlan {
+  int32_t F, B;
+  int32_t passes, radix_bits;      // digit width per pass
+  int32_t max_tiles;               // max tiles of one field (grid.x)
+  int32_t total_tiles;
+};
+struct SortBuffers {
+  const int32_t* ids;
+  const int32_t* offsets;          // [F][B+1]
+  int32_t* key[2];
+  int32_t* pay[2];
+  uint32_t* hist;                  // [total_tiles << radix_bits]
+};
+hipError_t launch_sort_pass(const SortPlan& pl, const SortBuffers& sb, int pass, const FieldPtr& fp,
+                            const TileBase& tb, Profiler* prof, hipStream_t s);
+
+struct SegArgs {
+  const int32_t* key;              // sorted row ids, field-major at fp.p[f]
+  const int32_t* pay;              // sample index of each sorted lookup
+  int32_t* tile_heads;             // [total_tiles + 1] heads per tile -> exclusive prefix
+  int32_t* ubase;                  // [F + 1] first unique of each field; ubase[F] = U
+  int32_t* uniq;                   // [U]
+  int32_t* segoff;                 // [U + F], field f's slice starts at ubase[f] + f
+  float* sample_w;                 // [B]
+  int32_t* long_count;             // [1]
+  int32_t* long_list;              // [cap]
+  float* G;                        // [U, D]
+  const float* dx;                 // [B, lddx]
+  int64_t lddx;
+  int32_t F, D, B, max_tiles, total_tiles, long_threshold, long_cap;
+};
+hipError_t launch_segments(const SegArgs& a, const FieldPtr& fp, const TileBase& tb,
+                           const ShardTab& tab, Profiler* prof, hipStream_t s);
+hipError_t launch_seg_reduce(const SegArgs& a, const FieldPtr& fp, int64_t nnz_total, Profiler* prof,
+                             hipStream_t s);
+
+// ---------------------------------------------------------------- optim.hip
+struct DenseAggArgs {
+  const float* grads;  // [K, P]
+  float* g;            // [P]
+  int64_t P;
+};
+hipError_t launch_dense_agg(const DenseAggArgs& a, const ShardTab& tab, hipStream_t s);
+
+struct SparseAdagradArgs {
+  void* tables;
+  float* state;
+  const float* G;
+  const int32_t* uniq;
+  const int32_t* ubase;  // [F+1]
+  int64_t R;
+  int32_t F, D, table_bf16, rowwise;
+  float lr, eps;
+  int64_t max_rows;      // upper bound on U (sizes the grid)
+};
+hipError_t launch_sparse_adagrad(const SparseAdagradArgs& a, hipStream_t s);
+
+struct DenseAdagradArgs {
+  float* p;
+  float* state;
+  const float* g;
+  int64_t P;
+  float lr, eps;
+  // bf16 operand copies of the hidden-layer weights: copy[l] mirrors p[w_off[l] .. +w_len[l])
+  int32_t n_copy;
+  int64_t w_off[ANTDT_MAX_LAYERS];
+  int64_t w_len[ANTDT_MAX_LAYERS];
+  bf16_t* copy[ANTDT_MAX_LAYERS];
+};
+hipError_t launch_dense_adagrad(const DenseAdagradArgs& a, hipStream_t s);
+
+struct AdamArgs {
+  float* p;
+  float* m;
+  float* v;
+  const float* g[16];
+  float w[16];
+  int32_t K;
+  int64_t n;
+  float lr, b1, b2, eps, inv_bc1, inv_bc2;
+};
+hipError_t launch_adam(const AdamArgs& a, hipStream_t s);
+
+}  // namespace antdt

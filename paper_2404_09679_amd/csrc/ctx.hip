@@ -1,0 +1,698 @@
+// C boundary: context, workspace layout, call-order checks and the launch
+// sequences of worker_step / aggregate / apply_update (see include/antdt.h).
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace antdt {
+
+struct ProfRec {
+  hipEvent_t start, stop;
+  int kid;
+};
+struct Profiler {
+  int mode = 0, sel = -1;
+  std::vector<ProfRec> recs;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+  double total_ms[KID_COUNT] = {};
+  int64_t launches[KID_COUNT] = {};
+  ProfRec* open = nullptr;
+};
+
+void prof_begin(Profiler* p, int kid, hipStream_t s) {
+  p->open = nullptr;
+  if (p->mode == 0 || (p->mode == 2 && kid != p->sel)) return;
+  ProfRec r;
+  r.kid = kid;
+  if (!p->pool.empty()) {
+    r.start = p->pool.back().first;
+    r.stop = p->pool.back().second;
+    p->pool.pop_back();
+  } else {
+    if (hipEventCreate(&r.start) != hipSuccess) return;
+    if (hipEventCreate(&r.stop) != hipSuccess) return;
+  }
+  (void)hipEventRecord(r.start, s);
+  p->recs.push_back(r);
+  p->open = &p->recs.back();
+}
+void prof_end(Profiler* p, int, hipStream_t s) {
+  if (p->open) (void)hipEventRecord(p->open->stop, s);
+  p->open = nullptr;
+}
+
+static void prof_drain(Profiler* p) {
+  for (auto& r : p->recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+      p->total_ms[r.kid] += ms;
+      p->launches[r.kid] += 1;
+    }
+    p->pool.push_back({r.start, r.stop});
+  }
+  p->recs.clear();
+}
+
+static const char* kKernelNames[KID_COUNT] = {
+    "pool",        "gemm_fwd",   "gemm_dgrad",     "gemm_wgrad",  "head",
+    "head_reduce", "bias_grad",  "sort_hist",      "sort_scan",   "sort_scatter",
+    "seg_heads",   "seg_scan",   "seg_emit",       "seg_reduce",  "seg_reduce_long",
+    "dense_agg",   "sparse_adagrad", "dense_adagrad", "adam"};
+
+}  // namespace antdt
+
+using namespace antdt;
+
+static thread_local std::string g_last_error;
+
+enum Stage { ST_CREATED = 0, ST_BOUND, ST_BATCH, ST_AGGREGATED };
+
+struct antdt_ctx {
+  antdt_model m;
+  std::string err;
+  Stage stage = ST_CREATED;
+  Profiler prof;
+  // derived sizes
+  int L = 0, FD = 0, in0 = 0, ldx = 0;
+  int act_bf16 = 0;
+  size_t act_size = 4;
+  int64_t P = 0;
+  int64_t w_off[ANTDT_MAX_LAYERS], b_off[ANTDT_MAX_LAYERS];
+  int width[ANTDT_MAX_LAYERS + 1];  // width[l] = layer_sizes[l]
+  int sort_passes = 1, radix_bits = 1;
+  int64_t max_tiles_total = 0;
+  int long_threshold = 64;
+  int64_t long_cap = 0;
+  size_t ws_bytes = 0;
+  // caller's buffers
+  void* tables = nullptr;
+  float* table_state = nullptr;
+  float* params = nullptr;
+  float* pstate = nullptr;
+  // workspace carve-up
+  char* x = nullptr;
+  char* h[ANTDT_MAX_LAYERS] = {};
+  char* dh[ANTDT_MAX_LAYERS] = {};
+  float *z = nullptr, *loss_s = nullptr, *dz = nullptr, *loss_k = nullptr, *dx = nullptr;
+  float *shard_grads = nullptr, *g_dense = nullptr, *sample_w = nullptr, *G = nullptr;
+  bf16_t* wb[ANTDT_MAX_LAYERS] = {};
+  int32_t *key[2] = {}, *pay[2] = {}, *tile_heads = nullptr, *ubase = nullptr, *uniq = nullptr;
+  int32_t *segoff = nullptr, *long_count = nullptr, *long_list = nullptr;
+  uint32_t* hist = nullptr;
+  // batch
+  const int32_t* ids = nullptr;
+  const int32_t* offsets = nullptr;
+  const float* dense = nullptr;
+  const float* labels = nullptr;
+  int64_t B = 0;
+  FieldPtr fp;
+  TileBase tb;
+  int max_tiles = 0, total_tiles = 0;
+  // shards
+  ShardTab tab;
+  bool have_shards = false;
+  int64_t shard_B = 0;
+  bool stepped[ANTDT_MAX_SHARDS] = {};
+  bool included[ANTDT_MAX_SHARDS] = {};
+  int sorted_buf = 0;
+};
+
+static int fail(antdt_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  g_last_error = msg;
+  return code;
+}
+#define HIP_TRY(c, expr)                                                                   \
+  do {                                                                                     \
+    hipError_t e__ = (expr);                                                               \
+    if (e__ != hipSuccess)                                                                 \
+      return fail(c, ANTDT_HIP_ERROR, std::string(#expr) + ": " + hipGetErrorString(e__)); \
+  } while (0)
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline Profiler* prof_of(antdt_ctx* c) { return c->prof.mode ? &c->prof : nullptr; }
+
+static bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+// Lays the workspace out; with base == nullptr only the size is computed.
+static size_t carve(antdt_ctx* c, char* base) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> char* {
+    char* p = base ? base + off : nullptr;
+    off = align_up(off + bytes, 256);
+    return p;
+  };
+  const antdt_model& m = c->m;
+  const int64_t Bm = m.max_batch, K = m.max_shards, N = m.max_nnz;
+  c->x = take((size_t)Bm * c->ldx * c->act_size);
+  for (int l = 1; l < c->L; ++l) {
+    c->h[l] = take((size_t)Bm * c->width[l] * c->act_size);
+    c->dh[l] = take((size_t)Bm * c->width[l] * c->act_size);
+  }
+  c->z = (float*)take(Bm * 4);
+  c->loss_s = (float*)take(Bm * 4);
+  c->dz = (float*)take(Bm * 4);
+  c->sample_w = (float*)take(Bm * 4);
+  c->loss_k = (float*)take(K * 4);
+  c->dx = (float*)take((size_t)Bm * c->FD * 4);
+  c->shard_grads = (float*)take((size_t)K * c->P * 4);
+  c->g_dense = (float*)take((size_t)c->P * 4);
+  if (c->act_bf16)
+    for (int l = 0; l + 1 < c->L; ++l) {
+      const int64_t rows = l == 0 ? c->ldx : c->width[l];
+      c->wb[l] = (bf16_t*)take((size_t)rows * c->width[l + 1] * 2);
+    }
+  for (int i = 0; i < 2; ++i) {
+    c->key[i] = (int32_t*)take((size_t)N * 4);
+    c->pay[i] = (int32_t*)take((size_t)N * 4);
+  }
+  c->hist = (uint32_t*)take((size_t)(c->max_tiles_total << c->radix_bits) * 4);
+  c->tile_heads = (int32_t*)take((size_t)(c->max_tiles_total + 1) * 4);
+  c->ubase = (int32_t*)take((size_t)(m.num_fields + 1) * 4);
+  c->uniq = (int32_t*)take((size_t)N * 4);
+  c->segoff = (int32_t*)take((size_t)(N + m.num_fields + 1) * 4);
+  c->long_count = (int32_t*)take(4);
+  c->long_list = (int32_t*)take((size_t)c->long_cap * 4);
+  c->G = (float*)take((size_t)N * m.dim * 4);
+  return off;
+}
+
+extern "C" {
+
+const char* antdt_last_error(const antdt_ctx* ctx) { return ctx ? ctx->err.c_str() : g_last_error.c_str(); }
+
+const char* antdt_kernel_name(int32_t kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : nullptr; }
+
+int antdt_create(const antdt_model* model, antdt_ctx** out) {
+  if (!model || !out) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_create: null argument");
+  const antdt_model& m = *model;
+  auto bad = [&](const char* what) { return fail(nullptr, ANTDT_INVALID_ARG, std::string("antdt_create: ") + what); };
+  if (m.num_fields < 1 || m.num_fields > ANTDT_MAX_FIELDS) return bad("num_fields out of range");
+  if (m.rows_per_field < 1 || m.rows_per_field >= (1ll << 31)) return bad("rows_per_field out of range");
+  if (m.table_dtype != ANTDT_F32 && m.table_dtype != ANTDT_BF16) return bad("table_dtype");
+  if (m.gemm_dtype != ANTDT_F32 && m.gemm_dtype != ANTDT_BF16) return bad("gemm_dtype");
+  if (m.adagrad_state != ANTDT_STATE_ELEMENTWISE && m.adagrad_state != ANTDT_STATE_ROWWISE) return bad("adagrad_state");
+  const int64_t row_bytes = (int64_t)m.dim * (m.table_dtype == ANTDT_BF16 ? 2 : 4);
+  if (m.dim < 4 || row_bytes < 16 || row_bytes > 1024 || !is_pow2(row_bytes)) return bad("dim: row must be 16..1024 bytes, a power of two");
+  if (m.num_dense < 0) return bad("num_dense");
+  if (m.num_layers < 1 || m.num_layers > ANTDT_MAX_LAYERS) return bad("num_layers out of range");
+  if ((int64_t)m.layer_sizes[0] != (int64_t)m.num_fields * m.dim + m.num_dense) return bad("layer_sizes[0] != num_fields*dim + num_dense");
+  if (m.layer_sizes[m.num_layers] != 1) return bad("last layer must have one output");
+  for (int l = 1; l < m.num_layers; ++l) {
+    if (m.layer_sizes[l] < 1) return bad("layer size");
+    if (m.gemm_dtype == ANTDT_BF16 && m.layer_sizes[l] % 8) return bad("bf16 GEMMs need hidden widths that are multiples of 8");
+  }
+  if (m.max_shards < 1 || m.max_shards > ANTDT_MAX_SHARDS) return bad("max_shards out of range");
+  if (m.max_batch < 1 || m.max_batch >= (1ll << 31)) return bad("max_batch out of range");
+  if (m.max_nnz < 0 || m.max_nnz >= (1ll << 31) - 4096) return bad("max_nnz out of range");
+  if (!(m.lr >= 0.f) || !(m.eps > 0.f)) return bad("lr must be >= 0 and eps > 0");
+
+  antdt_ctx* c = new antdt_ctx();
+  c->m = m;
+  c->L = m.num_layers;
+  c->FD = m.num_fields * m.dim;
+  c->in0 = m.layer_sizes[0];
+  c->ldx = (c->in0 + 7) / 8 * 8;
+  c->act_bf16 = m.gemm_dtype == ANTDT_BF16;
+  c->act_size = c->act_bf16 ? 2 : 4;
+  int64_t off = 0;
+  for (int l = 0; l <= c->L; ++l) c->width[l] = m.layer_sizes[l];
+  for (int l = 0; l < c->L; ++l) {
+    c->w_off[l] = off;
+    off += (int64_t)c->width[l] * c->width[l + 1];
+    c->b_off[l] = off;
+    off += c->width[l + 1];
+  }
+  c->P = off;
+  int bits = 1;
+  while ((1ll << bits) < m.rows_per_field) ++bits;
+  c->sort_passes = (bits + 9) / 10;
+  c->radix_bits = (bits + c->sort_passes - 1) / c->sort_passes;
+  c->max_tiles_total = m.max_nnz / 4096 + m.num_fields + 1;
+  c->long_cap = m.max_nnz / c->long_threshold + 1;
+  c->ws_bytes = carve(c, nullptr);
+  memset(&c->tab, 0, sizeof(c->tab));
+  *out = c;
+  return ANTDT_OK;
+}
+
+int antdt_destroy(antdt_ctx* ctx) {
+  if (!ctx) return ANTDT_OK;
+  prof_drain(&ctx->prof);
+  for (auto& e : ctx->prof.pool) {
+    (void)hipEventDestroy(e.first);
+    (void)hipEventDestroy(e.second);
+  }
+  delete ctx;
+  return ANTDT_OK;
+}
+
+int antdt_workspace_bytes(const antdt_ctx* ctx, size_t* bytes) {
+  if (!ctx || !bytes) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_workspace_bytes: null argument");
+  *bytes = ctx->ws_bytes;
+  return ANTDT_OK;
+}
+
+static int refresh_bf16_weights(antdt_ctx* c, hipStream_t s) {
+  if (!c->act_bf16) return ANTDT_OK;
+  for (int l = 0; l + 1 < c->L; ++l) {
+    CastArgs a;
+    a.src = c->params + c->w_off[l];
+    a.dst = c->wb[l];
+    a.n_src = (int64_t)c->width[l] * c->width[l + 1];
+    a.n_dst = (int64_t)(l == 0 ? c->ldx : c->width[l]) * c->width[l + 1];
+    HIP_TRY(c, launch_cast_bf16(a, s));
+  }
+  return ANTDT_OK;
+}
+
+int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params, float* mlp_state,
+               void* workspace, size_t workspace_bytes, void* stream) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_bind: null context");
+  if (!tables || !table_state || !mlp_params || !mlp_state || !workspace)
+    return fail(c, ANTDT_INVALID_ARG, "antdt_bind: null buffer");
+  if (workspace_bytes < c->ws_bytes) return fail(c, ANTDT_WORKSPACE_TOO_SMALL, "antdt_bind: workspace too small");
+  if (((uintptr_t)workspace & 255) || ((uintptr_t)tables & 15) || ((uintptr_t)table_state & 15) ||
+      ((uintptr_t)mlp_params & 15) || ((uintptr_t)mlp_state & 15))
+    return fail(c, ANTDT_INVALID_ARG, "antdt_bind: misaligned buffer (workspace 256 B, others 16 B)");
+  c->tables = tables;
+  c->table_state = table_state;
+  c->params = mlp_params;
+  c->pstate = mlp_state;
+  carve(c, (char*)workspace);
+  c->stage = ST_BOUND;
+  return refresh_bf16_weights(c, (hipStream_t)stream);
+}
+
+int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, const int32_t* offsets,
+                    const float* dense, const float* labels, int64_t B, void* stream) {
+  (void)stream;
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_batch: null context");
+  if (c->stage < ST_BOUND) return fail(c, ANTDT_BAD_STATE, "antdt_set_batch: call antdt_bind first");
+  if (!field_ptr || !offsets || !labels || (c->m.num_dense > 0 && !dense))
+    return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: null buffer");
+  if (B < 0 || B > c->m.max_batch) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: B out of range");
+  const int F = c->m.num_fields;
+  if (field_ptr[0] != 0) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: field_ptr[0] != 0");
+  for (int f = 0; f < F; ++f)
+    if (field_ptr[f + 1] < field_ptr[f]) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: field_ptr decreases");
+  if (field_ptr[F] > c->m.max_nnz) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: more lookups than max_nnz");
+  if (field_ptr[F] > 0 && !ids) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: null ids");
+  memset(&c->fp, 0, sizeof(c->fp));
+  memset(&c->tb, 0, sizeof(c->tb));
+  c->max_tiles = 0;
+  for (int f = 0; f < F; ++f) {
+    c->fp.p[f + 1] = field_ptr[f + 1];
+    const int tiles = (int)((field_ptr[f + 1] - field_ptr[f] + 4095) / 4096);
+    c->tb.t[f + 1] = c->tb.t[f] + tiles;
+    if (tiles > c->max_tiles) c->max_tiles = tiles;
+  }
+  for (int f = F + 1; f <= ANTDT_MAX_FIELDS; ++f) {
+    c->fp.p[f] = c->fp.p[F];
+    c->tb.t[f] = c->tb.t[F];
+  }
+  c->total_tiles = c->tb.t[F];
+  c->ids = ids;
+  c->offsets = offsets;
+  c->dense = dense;
+  c->labels = labels;
+  c->B = B;
+  c->stage = ST_BATCH;
+  memset(c->stepped, 0, sizeof(c->stepped));
+  return ANTDT_OK;
+}
+
+int antdt_assign_shard(antdt_ctx* c, int64_t B, int32_t K, const int64_t* sizes, const double* speed,
+                       int64_t* start_out, int64_t* len_out) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_assign_shard: null context");
+  if (K < 1 || K > c->m.max_shards) return fail(c, ANTDT_INVALID_ARG, "antdt_assign_shard: K out of range");
+  if (B < 0 || B > c->m.max_batch) return fail(c, ANTDT_INVALID_ARG, "antdt_assign_shard: B out of range");
+  std::vector<int64_t> len(K, 0);
+  if (sizes) {
+    int64_t tot = 0;
+    for (int k = 0; k < K; ++k) {
+      if (sizes[k] < 0) return fail(c, ANTDT_INVALID_ARG, "antdt_assign_shard: negative shard size");
+      len[k] = sizes[k];
+      tot += sizes[k];
+    }
+    if (tot != B) return fail(c, ANTDT_INVALID_ARG, "antdt_assign_shard: sizes do not sum to B");
+  } else if (speed) {
+    // Eq. 3: minimise z subject to z >= B_k / v_k, sum_k B_k = B.  Every worker can take
+    // floor(B v_k / sum v) - 1 samples without exceeding the continuous optimum B / sum v;
+    // the rest is handed out one sample at a time to the worker whose load after the
+    // addition is smallest (ties: lowest k), which is optimal for a max of linear costs.
+    long double tot_v = 0;
+    for (int k = 0; k < K; ++k) {
+      if (!(speed[k] > 0.0) || !isfinite(speed[k])) return fail(c, ANTDT_INVALID_ARG, "antdt_assign_shard: speed must be finite and > 0");
+      tot_v += speed[k];
+    }
+    int64_t given = 0;
+    for (int k = 0; k < K; ++k) {
+      int64_t b = (int64_t)floorl((long double)B * speed[k] / tot_v) - 1;
+      if (b < 0) b = 0;
+      len[k] = b;
+      given += b;
+    }
+    for (; given < B; ++given) {
+      int best = 0;
+      for (int k = 1; k < K; ++k) {
+        // (len[k]+1)/v_k < (len[best]+1)/v_best, cross-multiplied
+        const long double lhs = (long double)(len[k] + 1) * speed[best];
+        const long double rhs = (long double)(len[best] + 1) * speed[k];
+        if (lhs < rhs) best = k;
+      }
+      ++len[best];
+    }
+  } else {
+    const int64_t q = B / K, r = B % K;
+    for (int k = 0; k < K; ++k) len[k] = q + (k < r ? 1 : 0);
+  }
+  memset(&c->tab, 0, sizeof(c->tab));
+  c->tab.K = K;
+  int64_t s = 0;
+  for (int k = 0; k < K; ++k) {
+    c->tab.start[k] = (int32_t)s;
+    c->tab.len[k] = (int32_t)len[k];
+    if (start_out) start_out[k] = s;
+    if (len_out) len_out[k] = len[k];
+    s += len[k];
+  }
+  for (int k = K; k < ANTDT_MAX_SHARDS; ++k) c->tab.start[k] = (int32_t)s;
+  c->have_shards = true;
+  c->shard_B = B;
+  memset(c->stepped, 0, sizeof(c->stepped));
+  if (c->stage == ST_AGGREGATED) c->stage = ST_BATCH;
+  return ANTDT_OK;
+}
+
+// Forward and backward of shards [k0, k1) as one batched sequence of launches.
+static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream_t s) {
+  if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_worker_step: call antdt_set_batch first");
+  if (!c->have_shards || c->shard_B != c->B)
+    return fail(c, ANTDT_BAD_STATE, "antdt_worker_step: antdt_assign_shard with the batch's B is required");
+  Profiler* pr = prof_of(c);
+  const antdt_model& m = c->m;
+  const ShardTab& tab = c->tab;
+  const int64_t s0 = tab.start[k0];
+  const int64_t ns = (int64_t)tab.start[k1 - 1] + tab.len[k1 - 1] - s0;
+  const int L = c->L;
+  const size_t es = c->act_size;
+  {
+    PoolArgs a;
+    a.tables = c->tables; a.ids = c->ids; a.offsets = c->offsets; a.dense = c->dense; a.x = c->x;
+    a.F = m.num_fields; a.D = m.dim; a.num_dense = m.num_dense; a.ldx = c->ldx; a.B = (int32_t)c->B;
+    a.s0 = (int32_t)s0; a.ns = (int32_t)ns; a.R = m.rows_per_field;
+    a.table_bf16 = m.table_dtype == ANTDT_BF16; a.x_bf16 = c->act_bf16;
+    ProfScope ps(pr, KID_POOL, s);
+    HIP_TRY(c, launch_pool(a, c->fp, s));
+  }
+  auto act = [&](int l) -> char* { return l == 0 ? c->x : c->h[l]; };
+  auto ld = [&](int l) -> int64_t { return l == 0 ? c->ldx : c->width[l]; };
+  auto weight = [&](int l) -> const void* {
+    return c->act_bf16 ? (const void*)c->wb[l] : (const void*)(c->params + c->w_off[l]);
+  };
+  for (int l = 0; l + 1 < L; ++l) {  // hidden layers
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = act(l) + s0 * ld(l) * es; g.lda = ld(l); g.a_kc = 1;
+    g.B = weight(l); g.ldb = c->width[l + 1]; g.b_kc = 0;
+    g.C = c->h[l + 1] + s0 * c->width[l + 1] * es; g.ldc = c->width[l + 1];
+    g.bias = c->params + c->b_off[l];
+    g.M = (int32_t)ns; g.N = c->width[l + 1];
+    g.K = (l == 0 && c->act_bf16) ? c->ldx : c->width[l];
+    g.epi = EPI_BIAS_RELU; g.bf16_in = c->act_bf16; g.bf16_out = c->act_bf16;
+    ProfScope ps(pr, KID_GEMM_FWD, s);
+    HIP_TRY(c, launch_gemm(g, tab, s));
+  }
+  {
+    HeadArgs a;
+    memset(&a, 0, sizeof(a));
+    a.h = act(L - 1); a.ldh = ld(L - 1); a.width = c->width[L - 1];
+    a.w = c->params + c->w_off[L - 1]; a.b = c->params + c->b_off[L - 1];
+    a.labels = c->labels; a.z = c->z; a.loss_s = c->loss_s; a.dz = c->dz;
+    a.bf16_h = c->act_bf16;
+    if (L > 1) {
+      a.dh = c->dh[L - 1]; a.lddh = c->width[L - 1]; a.dh_cols = c->width[L - 1]; a.relu = 1; a.bf16_dh = c->act_bf16;
+    } else {
+      a.dh = c->dx; a.lddh = c->FD; a.dh_cols = c->FD; a.relu = 0; a.bf16_dh = 0;
+    }
+    a.k_begin = k0; a.k_end = k1;
+    {
+      ProfScope ps(pr, KID_HEAD, s);
+      HIP_TRY(c, launch_head(a, tab, s));
+    }
+    HeadReduceArgs r;
+    memset(&r, 0, sizeof(r));
+    r.h = act(L - 1); r.ldh = ld(L - 1); r.width = c->width[L - 1]; r.bf16_h = c->act_bf16;
+    r.dz = c->dz; r.loss_s = c->loss_s; r.grads = c->shard_grads; r.loss_k = c->loss_k; r.loss_out = loss_out;
+    r.P = c->P; r.w_off = c->w_off[L - 1]; r.b_off = c->b_off[L - 1]; r.k_begin = k0; r.k_end = k1;
+    ProfScope ps(pr, KID_HEAD_REDUCE, s);
+    HIP_TRY(c, launch_head_reduce(r, tab, s));
+  }
+  for (int l = L - 2; l >= 0; --l) {
+    {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
+      GemmArgs g;
+      memset(&g, 0, sizeof(g));
+      g.A = act(l); g.lda = ld(l); g.a_kc = 0;
+      g.B = c->dh[l + 1]; g.ldb = c->width[l + 1]; g.b_kc = 0;
+      g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
+      g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
+      g.epi = EPI_PLAIN; g.bf16_in = c->act_bf16; g.bf16_out = 0;
+      g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->P;
+      ProfScope ps(pr, KID_GEMM_WGRAD, s);
+      HIP_TRY(c, launch_gemm(g, tab, s));
+    }
+    {
+      BiasGradArgs b;
+      memset(&b, 0, sizeof(b));
+      b.dh = c->dh[l + 1]; b.lddh = c->width[l + 1]; b.width = c->width[l + 1]; b.bf16_dh = c->act_bf16;
+      b.grads = c->shard_grads; b.P = c->P; b.b_off = c->b_off[l]; b.k_begin = k0; b.k_end = k1;
+      ProfScope ps(pr, KID_BIAS_GRAD, s);
+      HIP_TRY(c, launch_bias_grad(b, tab, s));
+    }
+    {  // gradient w.r.t. act_l: through W_l, then the ReLU of layer l-1 (none for the input)
+      GemmArgs g;
+      memset(&g, 0, sizeof(g));
+      g.A = c->dh[l + 1] + s0 * c->width[l + 1] * es; g.lda = c->width[l + 1]; g.a_kc = 1;
+      g.B = weight(l); g.ldb = c->width[l + 1]; g.b_kc = 1;
+      g.M = (int32_t)ns; g.K = c->width[l + 1];
+      g.bf16_in = c->act_bf16;
+      if (l > 0) {
+        g.C = c->dh[l] + s0 * c->width[l] * es; g.ldc = c->width[l]; g.N = c->width[l];
+        g.mask = c->h[l] + s0 * c->width[l] * es; g.ldmask = c->width[l];
+        g.epi = EPI_RELU_MASK; g.bf16_out = c->act_bf16;
+      } else {
+        g.C = c->dx + s0 * c->FD; g.ldc = c->FD; g.N = c->FD;
+        g.epi = EPI_PLAIN; g.bf16_out = 0;
+      }
+      ProfScope ps(pr, KID_GEMM_DGRAD, s);
+      HIP_TRY(c, launch_gemm(g, tab, s));
+    }
+  }
+  for (int k = k0; k < k1; ++k) c->stepped[k] = true;
+  if (c->stage == ST_AGGREGATED) c->stage = ST_BATCH;
+  return ANTDT_OK;
+}
+
+int antdt_worker_step(antdt_ctx* c, int32_t k, float* loss_out, void* stream) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_worker_step: null context");
+  if (!c->have_shards || k < 0 || k >= c->tab.K) return fail(c, ANTDT_INVALID_ARG, "antdt_worker_step: shard index out of range");
+  return worker_range(c, k, k + 1, loss_out, (hipStream_t)stream);
+}
+
+int antdt_worker_step_all(antdt_ctx* c, float* loss_out, void* stream) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_worker_step_all: null context");
+  if (!c->have_shards) return fail(c, ANTDT_BAD_STATE, "antdt_worker_step_all: call antdt_assign_shard first");
+  return worker_range(c, 0, c->tab.K, loss_out, (hipStream_t)stream);
+}
+
+int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_aggregate: null context");
+  if (c->stage < ST_BATCH || !c->have_shards || c->shard_B != c->B)
+    return fail(c, ANTDT_BAD_STATE, "antdt_aggregate: set_batch, assign_shard and worker_step come first");
+  hipStream_t s = (hipStream_t)stream;
+  Profiler* pr = prof_of(c);
+  const antdt_model& m = c->m;
+  const int K = c->tab.K;
+  int64_t tot = 0;
+  for (int k = 0; k < K; ++k) {
+    c->included[k] = !shard_mask || shard_mask[k];
+    if (c->included[k]) {
+      if (c->tab.len[k] > 0 && !c->stepped[k])
+        return fail(c, ANTDT_BAD_STATE, "antdt_aggregate: an included shard has no worker_step result");
+      tot += c->tab.len[k];
+    } else if (c->tab.len[k] > 0) {
+      return fail(c, ANTDT_UNSUPPORTED, "antdt_aggregate: leaving out a non-empty shard is not implemented");
+    }
+  }
+  for (int k = 0; k < ANTDT_MAX_SHARDS; ++k)
+    c->tab.w[k] = (k < K && c->included[k] && tot > 0) ? (float)((double)c->tab.len[k] / (double)tot) : 0.0f;
+
+  SortPlan pl;
+  pl.F = m.num_fields; pl.B = (int32_t)c->B; pl.passes = c->sort_passes; pl.radix_bits = c->radix_bits;
+  pl.max_tiles = c->max_tiles; pl.total_tiles = c->total_tiles;
+  SortBuffers sb;
+  sb.ids = c->ids; sb.offsets = c->offsets;
+  sb.key[0] = c->key[0]; sb.key[1] = c->key[1]; sb.pay[0] = c->pay[0]; sb.pay[1] = c->pay[1];
+  sb.hist = c->hist;
+  for (int p = 0; p < pl.passes; ++p) HIP_TRY(c, launch_sort_pass(pl, sb, p, c->fp, c->tb, pr, s));
+  c->sorted_buf = (pl.passes - 1) & 1;
+
+  SegArgs a;
+  memset(&a, 0, sizeof(a));
+  a.key = c->key[c->sorted_buf]; a.pay = c->pay[c->sorted_buf];
+  a.tile_heads = c->tile_heads; a.ubase = c->ubase; a.uniq = c->uniq; a.segoff = c->segoff;
+  a.sample_w = c->sample_w; a.long_count = c->long_count; a.long_list = c->long_list;
+  a.G = c->G; a.dx = c->dx; a.lddx = c->FD;
+  a.F = m.num_fields; a.D = m.dim; a.B = (int32_t)c->B; a.max_tiles = c->max_tiles;
+  a.total_tiles = c->total_tiles; a.long_threshold = c->long_threshold; a.long_cap = (int32_t)c->long_cap;
+  HIP_TRY(c, launch_segments(a, c->fp, c->tb, c->tab, pr, s));
+  HIP_TRY(c, launch_seg_reduce(a, c->fp, c->fp.p[m.num_fields], pr, s));
+  {
+    DenseAggArgs d;
+    d.grads = c->shard_grads; d.g = c->g_dense; d.P = c->P;
+    ProfScope ps(pr, KID_DENSE_AGG, s);
+    HIP_TRY(c, launch_dense_agg(d, c->tab, s));
+  }
+  c->stage = ST_AGGREGATED;
+  return ANTDT_OK;
+}
+
+int antdt_apply_update(antdt_ctx* c, void* stream) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_apply_update: null context");
+  if (c->stage != ST_AGGREGATED) return fail(c, ANTDT_BAD_STATE, "antdt_apply_update: call antdt_aggregate first");
+  hipStream_t s = (hipStream_t)stream;
+  Profiler* pr = prof_of(c);
+  const antdt_model& m = c->m;
+  {
+    SparseAdagradArgs a;
+    a.tables = c->tables; a.state = c->table_state; a.G = c->G; a.uniq = c->uniq; a.ubase = c->ubase;
+    a.R = m.rows_per_field; a.F = m.num_fields; a.D = m.dim;
+    a.table_bf16 = m.table_dtype == ANTDT_BF16; a.rowwise = m.adagrad_state == ANTDT_STATE_ROWWISE;
+    a.lr = m.lr; a.eps = m.eps; a.max_rows = c->fp.p[m.num_fields];
+    ProfScope ps(pr, KID_SPARSE_ADAGRAD, s);
+    HIP_TRY(c, launch_sparse_adagrad(a, s));
+  }
+  {
+    DenseAdagradArgs a;
+    memset(&a, 0, sizeof(a));
+    a.p = c->params; a.state = c->pstate; a.g = c->g_dense; a.P = c->P; a.lr = m.lr; a.eps = m.eps;
+    if (c->act_bf16)
+      for (int l = 0; l + 1 < c->L; ++l) {
+        a.w_off[a.n_copy] = c->w_off[l];
+        a.w_len[a.n_copy] = (int64_t)c->width[l] * c->width[l + 1];
+        a.copy[a.n_copy] = c->wb[l];
+        ++a.n_copy;
+      }
+    ProfScope ps(pr, KID_DENSE_ADAGRAD, s);
+    HIP_TRY(c, launch_dense_adagrad(a, s));
+  }
+  c->stage = ST_BATCH;
+  memset(c->stepped, 0, sizeof(c->stepped));
+  return ANTDT_OK;
+}
+
+int antdt_dense_aggregate_adam(float* p, float* mm, float* v, const float* const* grads, const float* weights,
+                               int32_t K, int64_t n, float lr, float beta1, float beta2, float eps,
+                               int64_t step, void* stream) {
+  if (!p || !mm || !v || !grads || !weights) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: null argument");
+  if (K < 1 || K > 16) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: K must be 1..16");
+  if (n < 0 || step < 1) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: n >= 0 and step >= 1 required");
+  AdamArgs a;
+  memset(&a, 0, sizeof(a));
+  a.p = p; a.m = mm; a.v = v; a.K = K; a.n = n;
+  uintptr_t al = (uintptr_t)p | (uintptr_t)mm | (uintptr_t)v;
+  for (int k = 0; k < K; ++k) {
+    if (!grads[k]) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: null gradient buffer");
+    a.g[k] = grads[k];
+    a.w[k] = weights[k];
+    al |= (uintptr_t)grads[k];
+  }
+  if (al & 15) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: buffers must be 16-byte aligned");
+  a.lr = lr; a.b1 = beta1; a.b2 = beta2; a.eps = eps;
+  a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
+  a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+  HIP_TRY(nullptr, launch_adam(a, (hipStream_t)stream));
+  return ANTDT_OK;
+}
+
+int antdt_fill_tables(void* tables, int32_t dtype, int32_t F, int64_t R, int32_t D, float scale, void* stream) {
+  if (!tables || F < 1 || R < 1 || D < 1 || (dtype != ANTDT_F32 && dtype != ANTDT_BF16))
+    return fail(nullptr, ANTDT_INVALID_ARG, "antdt_fill_tables: invalid argument");
+  HIP_TRY(nullptr, launch_fill_tables(tables, dtype == ANTDT_BF16, F, R, D, scale, (hipStream_t)stream));
+  return ANTDT_OK;
+}
+
+int antdt_view_pooled(antdt_ctx* c, int32_t k, const void** x, int64_t* rows, int64_t* ldo, int32_t* dtype) {
+  if (!c || !x || !rows || !ldo || !dtype) return fail(c, ANTDT_INVALID_ARG, "antdt_view_pooled: null argument");
+  if (!c->have_shards || k < 0 || k >= c->tab.K) return fail(c, ANTDT_INVALID_ARG, "antdt_view_pooled: shard index out of range");
+  if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_pooled: nothing computed yet");
+  *x = c->x + (int64_t)c->tab.start[k] * c->ldx * c->act_size;
+  *rows = c->tab.len[k];
+  *ldo = c->ldx;
+  *dtype = c->act_bf16 ? ANTDT_BF16 : ANTDT_F32;
+  return ANTDT_OK;
+}
+
+int antdt_view_shard_grads(antdt_ctx* c, int32_t k, const float** dense, const float** dx, int64_t* ld_dx) {
+  if (!c || !dense || !dx || !ld_dx) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: null argument");
+  if (!c->have_shards || k < 0 || k >= c->tab.K) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: shard index out of range");
+  if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_shard_grads: nothing computed yet");
+  *dense = c->shard_grads + (int64_t)k * c->P;
+  *dx = c->dx + (int64_t)c->tab.start[k] * c->FD;
+  *ld_dx = c->FD;
+  return ANTDT_OK;
+}
+
+int antdt_view_dense_grad(antdt_ctx* c, const float** g) {
+  if (!c || !g) return fail(c, ANTDT_INVALID_ARG, "antdt_view_dense_grad: null argument");
+  if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_dense_grad: nothing computed yet");
+  *g = c->g_dense;
+  return ANTDT_OK;
+}
+
+int antdt_view_coalesced(antdt_ctx* c, int32_t f, const int32_t** unique_ids, const int32_t** seg_offsets,
+                         const int32_t** seg_samples, int64_t* num_unique, int64_t* nnz, const float** G,
+                         void* stream) {
+  if (!c || !unique_ids || !seg_offsets || !seg_samples || !num_unique || !nnz || !G)
+    return fail(c, ANTDT_INVALID_ARG, "antdt_view_coalesced: null argument");
+  if (f < 0 || f >= c->m.num_fields) return fail(c, ANTDT_INVALID_ARG, "antdt_view_coalesced: field out of range");
+  if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_coalesced: call antdt_aggregate first");
+  int32_t ub[2];
+  HIP_TRY(c, hipMemcpyAsync(ub, c->ubase + f, sizeof(ub), hipMemcpyDeviceToHost, (hipStream_t)stream));
+  HIP_TRY(c, hipStreamSynchronize((hipStream_t)stream));
+  *unique_ids = c->uniq + ub[0];
+  *seg_offsets = c->segoff + ub[0] + f;
+  *seg_samples = c->pay[c->sorted_buf] + c->fp.p[f];
+  *num_unique = ub[1] - ub[0];
+  *nnz = c->fp.p[f + 1] - c->fp.p[f];
+  *G = c->G + (int64_t)ub[0] * c->m.dim;
+  return ANTDT_OK;
+}
+
+int antdt_profile(antdt_ctx* c, int32_t mode, int32_t kernel_id) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_profile: null context");
+  if (mode < 0 || mode > 2 || (mode == 2 && (kernel_id < 0 || kernel_id >= KID_COUNT)))
+    return fail(c, ANTDT_INVALID_ARG, "antdt_profile: invalid mode or kernel id");
+  c->prof.mode = mode;
+  c->prof.sel = kernel_id;
+  return ANTDT_OK;
+}
+
+int antdt_profile_read(antdt_ctx* c, int32_t kid, int64_t* launches, double* total_ms) {
+  if (!c || !launches || !total_ms) return fail(c, ANTDT_INVALID_ARG, "antdt_profile_read: null argument");
+  if (kid < 0 || kid >= KID_COUNT) return fail(c, ANTDT_INVALID_ARG, "antdt_profile_read: kernel id out of range");
+  prof_drain(&c->prof);
+  *launches = c->prof.launches[kid];
+  *total_ms = c->prof.total_ms[kid];
+  c->prof.launches[kid] = 0;
+  c->prof.total_ms[kid] = 0.0;
+  return ANTDT_OK;
+}
+
+}  // extern "C"

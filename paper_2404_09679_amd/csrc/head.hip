@@ -1,0 +1,148 @@
+// Last (single-logit) layer, binary cross-entropy and the start of the backward
+// pass of the worker step, plus the per-shard reductions that are sums over the
+// samples of a shard (last-layer weight gradient, bias gradients, mean loss).
+// Every reduction runs in a fixed order, so results are bitwise repeatable.
+#include "common.h"
+
+namespace antdt {
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// One wavefront per sample: z = h . w + b, the sample's loss and dz, then dh = dz * w
+// (zeroed where the hidden activation is not positive).
+template <typename TH, typename TD>
+__global__ __launch_bounds__(256) void head_kernel(HeadArgs a, ShardTab tab) {
+  const int lane = threadIdx.x & 63;
+  const int64_t first = tab.start[a.k_begin];
+  const int64_t last = (int64_t)tab.start[a.k_end - 1] + tab.len[a.k_end - 1];
+  const int64_t s = first + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (s >= last) return;
+  int k = a.k_begin;
+  while (k + 1 < a.k_end && s >= (int64_t)tab.start[k] + tab.len[k]) ++k;
+  const float inv_bk = 1.0f / (float)tab.len[k];
+  const TH* h = reinterpret_cast<const TH*>(a.h) + s * a.ldh;
+  float part = 0.0f;
+  for (int j = lane; j < a.width; j += 64) part = fmaf(to_f32(h[j]), a.w[j], part);
+  const float z = wave_sum(part) + a.b[0];
+  const float y = a.labels[s];
+  const float e = expf(-fabsf(z));
+  const float loss = fmaxf(z, 0.0f) - z * y + log1pf(e);
+  const float sig = z >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+  const float dz = (sig - y) * inv_bk;
+  if (lane == 0) {
+    a.z[s] = z;
+    a.loss_s[s] = loss;
+    a.dz[s] = dz;
+  }
+  TD* dh = reinterpret_cast<TD*>(a.dh) + s * a.lddh;
+  for (int j = lane; j < a.dh_cols; j += 64) {
+    float g = dz * a.w[j];
+    if (a.relu && !(to_f32(h[j]) > 0.0f)) g = 0.0f;
+    dh[j] = from_f32<TD>(g);
+  }
+}
+
+// Block (64 columns x 4 sample lanes) of shard k = k_begin + blockIdx.y:
+//   dW_last[j] = sum_s h[s, j] * dz[s];  block 0 also: db_last = sum_s dz[s], loss_k = mean loss.
+template <typename TH>
+__global__ __launch_bounds__(256) void head_reduce_kernel(HeadReduceArgs a, ShardTab tab) {
+  __shared__ float red[4][64];
+  const int k = a.k_begin + blockIdx.y;
+  const int64_t s0 = tab.start[k];
+  const int n = tab.len[k];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + tx;
+  float* g = a.grads + (int64_t)k * a.P;
+  float acc = 0.0f;
+  if (j < a.width) {
+    const TH* h = reinterpret_cast<const TH*>(a.h) + s0 * a.ldh + j;
+    for (int s = ty; s < n; s += 4) acc = fmaf(to_f32(h[(int64_t)s * a.ldh]), a.dz[s0 + s], acc);
+  }
+  red[ty][tx] = acc;
+  __syncthreads();
+  if (ty == 0 && j < a.width) g[a.w_off + j] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
+  if (blockIdx.x == 0) {
+    __syncthreads();
+    float sdz = 0.0f, sl = 0.0f;
+    for (int s = threadIdx.x; s < n; s += 256) {
+      sdz += a.dz[s0 + s];
+      sl += a.loss_s[s0 + s];
+    }
+    sdz = wave_sum(sdz);
+    sl = wave_sum(sl);
+    if (tx == 0) {
+      red[0][ty] = sdz;
+      red[1][ty] = sl;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      g[a.b_off] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+      const float lk = n > 0 ? ((red[1][0] + red[1][1]) + (red[1][2] + red[1][3])) / (float)n : 0.0f;
+      a.loss_k[k] = lk;
+      if (a.loss_out) a.loss_out[k - a.k_begin] = lk;
+    }
+  }
+}
+
+// db[k][o] = sum over the samples of shard k of dh[s, o].
+template <typename TD>
+__global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs a, ShardTab tab) {
+  __shared__ float red[4][64];
+  const int k = a.k_begin + blockIdx.y;
+  const int64_t s0 = tab.start[k];
+  const int n = tab.len[k];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + tx;
+  float acc = 0.0f;
+  if (j < a.width) {
+    const TD* d = reinterpret_cast<const TD*>(a.dh) + s0 * a.lddh + j;
+    int s = ty;
+    for (; s + 12 < n; s += 16) {
+      const float v0 = to_f32(d[(int64_t)s * a.lddh]), v1 = to_f32(d[(int64_t)(s + 4) * a.lddh]);
+      const float v2 = to_f32(d[(int64_t)(s + 8) * a.lddh]), v3 = to_f32(d[(int64_t)(s + 12) * a.lddh]);
+      acc += (v0 + v1) + (v2 + v3);
+    }
+    for (; s < n; s += 4) acc += to_f32(d[(int64_t)s * a.lddh]);
+  }
+  red[ty][tx] = acc;
+  __syncthreads();
+  if (ty == 0 && j < a.width)
+    a.grads[(int64_t)k * a.P + a.b_off + j] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
+}
+
+}  // namespace
+
+hipError_t launch_head(const HeadArgs& a, const ShardTab& tab, hipStream_t s) {
+  const int64_t first = tab.start[a.k_begin];
+  const int64_t last = (int64_t)tab.start[a.k_end - 1] + tab.len[a.k_end - 1];
+  if (last <= first) return hipSuccess;
+  dim3 grid((unsigned)((last - first + 3) / 4)), block(256);
+  if (a.bf16_h) {
+    if (a.bf16_dh) hipLaunchKernelGGL((head_kernel<bf16_t, bf16_t>), grid, block, 0, s, a, tab);
+    else hipLaunchKernelGGL((head_kernel<bf16_t, float>), grid, block, 0, s, a, tab);
+  } else {
+    hipLaunchKernelGGL((head_kernel<float, float>), grid, block, 0, s, a, tab);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_head_reduce(const HeadReduceArgs& a, const ShardTab& tab, hipStream_t s) {
+  dim3 grid((a.width + 63) / 64, a.k_end - a.k_begin), block(256);
+  if (a.bf16_h) hipLaunchKernelGGL(head_reduce_kernel<bf16_t>, grid, block, 0, s, a, tab);
+  else hipLaunchKernelGGL(head_reduce_kernel<float>, grid, block, 0, s, a, tab);
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_grad(const BiasGradArgs& a, const ShardTab& tab, hipStream_t s) {
+  dim3 grid((a.width + 63) / 64, a.k_end - a.k_begin), block(256);
+  if (a.bf16_dh) hipLaunchKernelGGL(bias_grad_kernel<bf16_t>, grid, block, 0, s, a, tab);
+  else hipLaunchKernelGGL(bias_grad_kernel<float>, grid, block, 0, s, a, tab);
+  return hipGetLastError();
+}
+
+}  // namespace antdt

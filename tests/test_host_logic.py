@@ -1,0 +1,129 @@
+"""CPU-only checks of the library's host side: it loads, exports every symbol the header
+declares, validates arguments and call order, and splits batches as Section V-C.1 /
+Section VI-A (Eq. 3) require.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+import workload as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = pytest.importorskip("paper_2404_09679_amd", reason="build the library first (python -m paper_2404_09679_amd.build)")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "antdt.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(antdt_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(A.binding.EXPORTS)
+    for name in declared:
+        assert hasattr(A.lib, name), name
+
+
+def test_model_struct_matches_header_layout():
+    # int32, (pad), int64, 4 x int32 ... : the ctypes mirror must have the C layout
+    assert C.sizeof(A.Model) == 104
+    assert A.Model.rows_per_field.offset == 8 and A.Model.layer_sizes.offset == 36
+    assert A.Model.max_batch.offset == 88 and A.Model.max_nnz.offset == 96
+
+
+def good_model():
+    return A.model_from_config(wl.CONFIGS[1])
+
+
+@pytest.mark.parametrize("field,value", [("num_fields", 0), ("num_fields", 129), ("rows_per_field", 0),
+                                         ("dim", 6), ("dim", 3), ("table_dtype", 2), ("num_layers", 0),
+                                         ("num_layers", 9), ("max_shards", 65), ("max_batch", 0), ("eps", 0.0),
+                                         ("num_dense", 12)])
+def test_create_rejects_bad_models(field, value):
+    m = good_model()
+    setattr(m, field, value)
+    with pytest.raises(A.AntdtError) as e:
+        A.Context(m)
+    assert e.value.code == -1 and "antdt_create" in str(e.value)
+
+
+def test_create_rejects_bad_layers():
+    m = good_model()
+    m.layer_sizes[m.num_layers] = 2
+    with pytest.raises(A.AntdtError):
+        A.Context(m)
+    m = A.model_from_config(wl.scaled(wl.CONFIGS[1], layer_sizes=(141, 60, 1), gemm_dtype="bf16"))
+    with pytest.raises(A.AntdtError) as e:
+        A.Context(m)
+    assert "multiples of 8" in str(e.value)
+
+
+def test_call_order_is_checked_before_any_gpu_work():
+    ctx = A.Context(good_model())
+    assert ctx.workspace_bytes() > 0
+    fp = (C.c_int64 * 9)()
+    rc = A.lib.antdt_set_batch(ctx._h, None, fp, None, None, None, 4, None)
+    assert rc == -2 and b"antdt_bind" in A.lib.antdt_last_error(ctx._h)
+    assert A.lib.antdt_worker_step(ctx._h, 0, None, None) == -1      # no shards yet
+    ctx.assign_shard(256, 4)
+    assert A.lib.antdt_worker_step(ctx._h, 0, None, None) == -2      # no batch yet
+    assert A.lib.antdt_worker_step(ctx._h, 4, None, None) == -1
+    assert A.lib.antdt_aggregate(ctx._h, None, None) == -2
+    assert A.lib.antdt_apply_update(ctx._h, None) == -2
+    assert A.lib.antdt_bind(ctx._h, None, None, None, None, None, 0, None) == -1
+    assert A.lib.antdt_dense_aggregate_adam(None, None, None, None, None, 8, 4, 0.1, 0.9, 0.99, 1e-8, 1, None) == -1
+
+
+def test_assign_shard_explicit_and_equal():
+    ctx = A.Context(A.model_from_config(wl.CONFIGS[3]))
+    sizes = wl.CONFIGS[3].shard_sizes
+    got = ctx.assign_shard(sum(sizes), len(sizes), sizes=sizes)
+    assert got == oracle.explicit_split(sizes)
+    assert ctx.assign_shard(10, 4) == oracle.equal_split(10, 4) == [(0, 3), (3, 3), (6, 2), (8, 2)]
+    assert ctx.assign_shard(0, 3) == [(0, 0)] * 3
+    for bad in ([5, 5, 5], [-1, 11, 0]):
+        with pytest.raises(A.AntdtError) as e:
+            ctx.assign_shard(10, 3, sizes=bad)
+        assert e.value.code == -1
+    with pytest.raises(A.AntdtError):
+        ctx.assign_shard(10, 9)                     # K > max_shards
+    with pytest.raises(A.AntdtError):
+        ctx.assign_shard(10, 2, speed=[1.0, 0.0])   # speeds must be positive
+
+
+@pytest.mark.parametrize("speeds", [(1.0, 1.0, 1.0), (1.0, 2.0, 4.0), (3.0, 1.0), (0.5, 1.5, 1.0, 2.0),
+                                    (1.0, 1.0, 3.0, 3.0), (7.0,), (0.3, 0.7, 1.9)])
+def test_assign_shard_speed_mode_is_optimal_for_eq3(speeds):
+    """ADJUST_BS: the split minimises max_k B_k / v_k over all integer splits (brute force)."""
+    ctx = A.Context(A.model_from_config(wl.CONFIGS[1]))
+    for B in range(0, 17):
+        got = ctx.assign_shard(B, len(speeds), speed=speeds)
+        lens = [n for _, n in got]
+        assert sum(lens) == B and all(n >= 0 for n in lens)
+        assert [s for s, _ in got] == list(np.cumsum([0] + lens[:-1]))
+        z, arg = oracle.minmax_split_bruteforce(B, speeds)
+        assert oracle.minmax_objective(lens, speeds) == z
+        assert tuple(lens) in arg
+        assert z >= Fraction(B) / sum(Fraction(v) for v in speeds)
+
+
+def test_assign_shard_speed_mode_large_batch():
+    ctx = A.Context(A.model_from_config(wl.CONFIGS[3]))
+    speeds = [1.0, 1.5, 2.0, 3.0, 4.0, 5.0, 6.0, 8.0]
+    B = 15616
+    lens = [n for _, n in ctx.assign_shard(B, 8, speed=speeds)]
+    assert sum(lens) == B
+    z = max(n / v for n, v in zip(lens, speeds))
+    # within one sample of the continuous optimum on every worker
+    assert all(abs(n - B * v / sum(speeds)) <= 1.0 for n, v in zip(lens, speeds))
+    # no single move improves the maximum
+    for i in range(8):
+        for j in range(8):
+            if i != j and lens[i] > 0:
+                moved = list(lens)
+                moved[i] -= 1
+                moved[j] += 1
+                assert max(n / v for n, v in zip(moved, speeds)) >= z - 1e-12
+    # equal speeds reproduce the initial B/n split
+    assert [n for _, n in ctx.assign_shard(4096, 8, speed=[2.5] * 8)] == [512] * 8
