@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Throughput of one BSP Parameter-Server training iteration on one MI355X.
+
+A step is the whole hot path on one fresh synthetic batch that is already resident in
+HBM: set_batch + worker_step for all K shards + aggregate + apply_update (parameters are
+really updated every step; eight distinct batches are rotated).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def _bytes_and_flops(cfg, stats, model):
+    """Algorithmic (compulsory) HBM bytes, or flops, of one step per kernel class."""
+    F, D, B, K = cfg.num_fields, cfg.dim, stats["B"], stats["K"]
+    nnz, U, P = stats["nnz"], stats["U"], cfg.num_params
+    e = 2 if cfg.table_dtype == "bf16" else 4
+    es = 2 if cfg.gemm_dtype == "bf16" else 4
+    ldx = (cfg.input_width + 7) // 8 * 8
+    state_row = 4 if cfg.adagrad_state == "rowwise" else 4 * D
+    s = cfg.layer_sizes
+    L = len(s) - 1
+    fwd = sum(2 * B * s[l] * s[l + 1] for l in range(L - 1))
+    dgrad = sum(2 * B * s[l + 1] * (s[l] if l > 0 else F * D) for l in range(L - 1))
+    passes = model["sort_passes"]
+    out = {
+        "pool": ("hbm", 4 * nnz + 4 * F * (B + 1) + U * D * e + B * ldx * es),
+        "gemm_fwd": ("mfma", fwd),
+        "gemm_dgrad": ("mfma", dgrad),
+        "gemm_wgrad": ("mfma", fwd),
+        "sort_hist": ("hbm", passes * 4 * nnz),
+        "sort_scatter": ("hbm", 4 * nnz + 8 * nnz + (passes - 1) * 16 * nnz),
+        "seg_heads": ("hbm", 4 * nnz),
+        "seg_emit": ("hbm", 4 * nnz + 8 * U),
+        "seg_reduce": ("hbm", 4 * nnz + B * F * D * 4 + U * D * 4),
+        "sparse_adagrad": ("hbm", U * (2 * D * e + 2 * state_row + 4 * D)),
+        "dense_agg": ("hbm", (K + 1) * P * 4),
+        "dense_adagrad": ("hbm", P * (5 * 4 + (2 if cfg.gemm_dtype == "bf16" else 0))),
+    }
+    return out
+
+
+def run_ranking(args, cfg_id):
+    import numpy as np
+    import torch
+
+    import paper_2404_09679_amd as A
+    import workload as wl
+
+    cfg = wl.CONFIGS[cfg_id]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    F, R, D = cfg.num_fields, cfg.rows_per_field, cfg.dim
+    tdtype = torch.bfloat16 if cfg.table_dtype == "bf16" else torch.float32
+    tables = torch.empty((F * R, D), dtype=tdtype, device=dev)
+    A.fill_tables(tables, F, R, D, 0.05)
+    state = torch.zeros((F * R, D) if cfg.adagrad_state == "elementwise" else (F * R,), dtype=torch.float32,
+                        device=dev)
+    params = torch.from_numpy(wl.make_mlp_params(cfg)).to(dev)
+    pstate = torch.zeros_like(params)
+    nb = 8
+    batches = [wl.make_batch(cfg, i) for i in range(nb)]
+    max_nnz = max(int(b.field_ptr[-1]) for b in batches)
+    model = A.model_from_config(cfg, max_nnz=max_nnz)
+    ctx = A.Context(model)
+    ctx.bind(tables, state, params, pstate)
+    dbatches = []
+    for b in batches:
+        dbatches.append((torch.from_numpy(b.ids).to(dev), b.field_ptr, torch.from_numpy(b.offsets).to(dev),
+                         torch.from_numpy(b.dense).to(dev) if cfg.num_dense else None,
+                         torch.from_numpy(b.labels).to(dev)))
+    K, B = cfg.num_shards, cfg.batch
+    loss = torch.zeros(K, dtype=torch.float32, device=dev)
+    ctx.assign_shard(B, K, sizes=cfg.shard_sizes)
+
+    def step(i):
+        ids, fp, off, dense, labels = dbatches[i % nb]
+        ctx.set_batch(ids, fp, off, dense, labels)
+        ctx.worker_step_all(loss)
+        ctx.aggregate()
+        ctx.apply_update()
+
+    names = A.kernel_names()
+    # warm-up, with every kernel class timed by HIP events on the launch stream
+    ctx.profile(1)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    per_class = {}
+    for kid, name in enumerate(names):
+        n, ms = ctx.profile_read(kid)
+        if n:
+            per_class[name] = (n / max(args.warmup, 1), ms / max(args.warmup, 1))
+    dominant = max(per_class, key=lambda k: per_class[k][1]) if per_class else names[0]
+    # timed region: events only around the dominant class
+    ctx.profile(2, names.index(dominant))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_dom, ms_dom = ctx.profile_read(names.index(dominant))
+    ctx.profile(0)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = B / (ms_per_step * 1e-3)
+
+    stats = dict(B=B, K=K, nnz=float(np.mean([b.field_ptr[-1] for b in batches])),
+                 U=float(np.mean([sum(len(np.unique(b.field_ids(f))) for f in range(F)) for b in batches])))
+    bits = max(1, int(np.ceil(np.log2(R))))
+    table = _bytes_and_flops(cfg, stats, dict(sort_passes=(bits + 9) // 10))
+    launches_per_step = n_dom / args.steps
+    avg_ms = ms_dom / max(n_dom, 1)
+    bound, per_step = table.get(dominant, ("hbm", 0.0))
+    per_launch = per_step / max(launches_per_step, 1e-9)
+    if bound == "hbm":
+        achieved = per_launch / (avg_ms * 1e-3) / 1e9
+        roof = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                    traffic=None)
+    else:
+        achieved = per_launch / (avg_ms * 1e-3) / 1e12
+        roof = dict(bound="mfma", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None)
+    roof.update(kernel=dominant, avg_launch_us=avg_ms * 1e3, launches_per_step=launches_per_step,
+                algorithmic_per_launch=per_launch)
+    total_bytes = sum(v for k, (b, v) in table.items() if b == "hbm")
+    breakdown = {k: round(v[1] * 1e3, 2) for k, v in sorted(per_class.items(), key=lambda kv: -kv[1][1])}
+    out = {
+        "metric": "training samples/sec per iteration (1 GPU)", "value": value, "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.gemm_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{cfg_id - 1}] {cfg.name}: F={F} R={R} D={D} {cfg.table_dtype} tables, "
+                               f"B={B} as {K} shards, MLP {'-'.join(map(str, cfg.layer_sizes))} "
+                               f"{cfg.gemm_dtype} GEMM, Adagrad", "global_batch": B, "shards": K,
+                   "lookups_per_step": stats["nnz"], "unique_rows_per_step": stats["U"]},
+        "roofline": roof,
+        "hbm_composite": {"algorithmic_bytes_per_step": total_bytes,
+                          "frac_of_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "kernel_us_per_step": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, batches[0])
+    return out
+
+
+def cpu_baseline(cfg, batch):
+    """The oracle, as it stands, on one iteration of the same workload (host cores).
+
+    The tables are restricted to the rows the batch touches (ids relabelled in order), which
+    changes no arithmetic and avoids materialising the full tables on the host."""
+    import numpy as np
+
+    import oracle
+    import workload as wl
+    from threadpoolctl import threadpool_info
+
+    F, D = cfg.num_fields, cfg.dim
+    uniq = [np.unique(batch.field_ids(f)) for f in range(F)]
+    Rc = max(len(u) for u in uniq)
+    ids = batch.ids.copy()
+    for f in range(F):
+        lo, hi = batch.field_ptr[f], batch.field_ptr[f + 1]
+        ids[lo:hi] = np.searchsorted(uniq[f], batch.field_ids(f)).astype(np.int32)
+    cb = wl.Batch(ids, batch.field_ptr, batch.offsets, batch.dense, batch.labels)
+    tabs = []
+    for f in range(F):
+        t = np.zeros((Rc, D), np.float32)
+        t[:len(uniq[f])] = wl.table_rows_f32(cfg, f, uniq[f])
+        tabs.append(t)
+    state = [np.zeros((Rc, D) if cfg.adagrad_state == "elementwise" else (Rc,), np.float32) for _ in range(F)]
+    flat = wl.make_mlp_params(cfg)
+    layers = wl.split_params(cfg, flat)
+    lstate = wl.split_params(cfg, np.zeros_like(flat))
+    model = oracle.Model(F, Rc, D, cfg.num_dense, tuple(cfg.layer_sizes), cfg.adagrad_state == "rowwise",
+                         cfg.table_dtype == "bf16", cfg.gemm_dtype == "bf16", cfg.lr, cfg.eps)
+    t0 = time.perf_counter()
+    res = [oracle.worker_step(model, tabs, layers, cb, s, n) for s, n in wl.shard_slices(cfg.shard_sizes)]
+    agg = oracle.aggregate(model, cb, res)
+    oracle.apply_update(model, tabs, state, layers, lstate, agg)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": cfg.batch / dt, "unit": "samples/s", "cores": threads, "kind": "oracle",
+            "seconds": dt,
+            "sample": f"one full iteration of the same workload (B={cfg.batch}, {cfg.num_shards} shards), "
+                      "numpy float64, tables restricted to the touched rows"}
+
+
+def run_dense(args):
+    import numpy as np
+    import torch
+
+    import paper_2404_09679_amd as A
+    import workload as wl
+
+    dc = wl.DENSE_CONFIG
+    dev = "cuda:0"
+    n, K = dc.n, dc.num_buffers
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(dc.seed)
+    p = torch.randn(n, device=dev, generator=gen) * dc.param_std
+    m, v = torch.zeros_like(p), torch.zeros_like(p)
+    grads = [torch.randn(n, device=dev, generator=gen) * dc.grad_std for _ in range(K)]
+    w = [1.0 / K] * K
+    step_no = 0
+    for _ in range(args.warmup):
+        step_no += 1
+        A.dense_aggregate_adam(p, m, v, grads, w, dc.lr, dc.beta1, dc.beta2, dc.eps, step_no)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step_no += 1
+        ev[i][0].record()
+        A.dense_aggregate_adam(p, m, v, grads, w, dc.lr, dc.beta1, dc.beta2, dc.eps, step_no)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    avg_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    nbytes = (K + 3) * 4 * n + 3 * 4 * n
+    achieved = nbytes / (avg_ms * 1e-3) / 1e9
+    return {
+        "metric": "dense weighted-average + Adam steps/sec (1 GPU)", "value": 1e3 / ms_per_step, "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[4] {dc.name}: {K} gradient buffers x 2^28 fp32, fused Adam"},
+        "roofline": dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                         frac=achieved / HBM_PEAK_GBS, traffic=None, kernel="adam", avg_launch_us=avg_ms * 1e3,
+                         algorithmic_per_launch=nbytes),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the K workers are shards on that device); "
+                 "use --gpus 1")
+    if args.workload == "cfg5":
+        out = run_dense(args)
+    else:
+        out = run_ranking(args, int(args.workload[3:]))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

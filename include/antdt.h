@@ -183,11 +183,13 @@ int antdt_apply_update(antdt_ctx* ctx, void* stream);
  *   p -= lr * (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps),
  * fused in one pass.  p, m, v: DEVICE fp32 [n], updated in place.  grads: HOST array of K
  * DEVICE pointers to fp32 [n] (1 <= K <= 16).  weights: HOST fp32 [K].  step >= 1.
- * All device pointers 16-byte aligned.  Context-free.
+ * The hyper-parameters are doubles so that 1-b1, 1-b2 and the bias corrections are formed
+ * exactly before being rounded to the kernel's fp32.  All device pointers 16-byte aligned.
+ * Context-free.
  */
 int antdt_dense_aggregate_adam(float* p, float* m, float* v, const float* const* grads,
-                               const float* weights, int32_t K, int64_t n, float lr, float beta1,
-                               float beta2, float eps, int64_t step, void* stream);
+                               const float* weights, int32_t K, int64_t n, double lr, double beta1,
+                               double beta2, double eps, int64_t step, void* stream);
 
 /*
  * Fill embedding tables with their procedural initial values (input generation, not part

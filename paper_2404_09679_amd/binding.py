@@ -58,8 +58,9 @@ def _load():
     lib.antdt_worker_step_all.argtypes = [vp, vp, vp]
     lib.antdt_aggregate.argtypes = [vp, C.POINTER(C.c_uint8), vp]
     lib.antdt_apply_update.argtypes = [vp, vp]
+    f64 = C.c_double
     lib.antdt_dense_aggregate_adam.argtypes = [vp, vp, vp, C.POINTER(vp), C.POINTER(f32), i32, i64,
-                                               f32, f32, f32, f32, i64, vp]
+                                               f64, f64, f64, f64, i64, vp]
     lib.antdt_fill_tables.argtypes = [vp, i32, i32, i64, i32, f32, vp]
     lib.antdt_view_pooled.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)]
     lib.antdt_view_shard_grads.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64)]

@@ -242,7 +242,7 @@ struct AdamArgs {
   float w[16];
   int32_t K;
   int64_t n;
-  float lr, b1, b2, eps, inv_bc1, inv_bc2;
+  float lr, b1, b2, c1, c2, eps, inv_bc1, inv_bc2;  // c = 1 - b, formed in double on the host
 };
 hipError_t launch_adam(const AdamArgs& a, hipStream_t s);
 

@@ -598,11 +598,12 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
 }
 
 int antdt_dense_aggregate_adam(float* p, float* mm, float* v, const float* const* grads, const float* weights,
-                               int32_t K, int64_t n, float lr, float beta1, float beta2, float eps,
+                               int32_t K, int64_t n, double lr, double beta1, double beta2, double eps,
                                int64_t step, void* stream) {
-  if (!p || !mm || !v || !grads || !weights) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: null argument");
   if (K < 1 || K > 16) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: K must be 1..16");
   if (n < 0 || step < 1) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: n >= 0 and step >= 1 required");
+  if (n == 0) return ANTDT_OK;  // nothing to do; empty buffers may be null
+  if (!p || !mm || !v || !grads || !weights) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: null argument");
   AdamArgs a;
   memset(&a, 0, sizeof(a));
   a.p = p; a.m = mm; a.v = v; a.K = K; a.n = n;
@@ -614,9 +615,10 @@ int antdt_dense_aggregate_adam(float* p, float* mm, float* v, const float* const
     al |= (uintptr_t)grads[k];
   }
   if (al & 15) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_dense_aggregate_adam: buffers must be 16-byte aligned");
-  a.lr = lr; a.b1 = beta1; a.b2 = beta2; a.eps = eps;
-  a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
-  a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+  a.lr = (float)lr; a.b1 = (float)beta1; a.b2 = (float)beta2; a.eps = (float)eps;
+  a.c1 = (float)(1.0 - beta1); a.c2 = (float)(1.0 - beta2);
+  a.inv_bc1 = (float)(1.0 / (1.0 - pow(beta1, (double)step)));
+  a.inv_bc2 = (float)(1.0 / (1.0 - pow(beta2, (double)step)));
   HIP_TRY(nullptr, launch_adam(a, (hipStream_t)stream));
   return ANTDT_OK;
 }

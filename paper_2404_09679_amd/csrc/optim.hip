@@ -108,7 +108,7 @@ template <int K>
 __global__ __launch_bounds__(256) void adam_kernel(AdamArgs a) {
   const int64_t n4 = a.n >> 2;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  const float c1 = 1.0f - a.b1, c2 = 1.0f - a.b2;
+  const float c1 = a.c1, c2 = a.c2;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
     f32x4 g = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll

@@ -40,9 +40,27 @@ def make_inputs(cfg, nonzero_state=False, batch_index=0):
     return tables, state, flat, fstate, batch
 
 
-def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, tol_struct_float=None,
+def assert_step_within_bound(step_gpu, step_ref, g_ref, cfg, tol, what):
+    """End-to-end bound on an Adagrad step.  step = lr*g/(sqrt(S+g^2)+eps) has
+    |d step / d g| <= lr/(|g|+eps), so a gradient that is within delta = tol*max|g| of the
+    oracle's moves the step by at most lr*delta/(|g|-delta+eps) (large only where |g| ~ eps),
+    on top of the tolerance on the step itself."""
+    g = np.abs(np.asarray(g_ref, dtype=np.float64))
+    delta = tol * (g.max() if g.size else 0.0)
+    bound = cfg.lr * delta / (np.maximum(g - delta, 0.0) + cfg.eps) + tol * cfg.lr
+    err = np.abs(np.asarray(step_gpu, np.float64) - np.asarray(step_ref, np.float64))
+    worst = float((err / bound).max()) if err.size else 0.0
+    assert worst <= 1.0, f"{what}: step error is {worst:.2f}x the bound"
+    # and the bulk agrees tightly: all but the |g| ~ eps elements
+    big = g > 1e3 * max(delta, cfg.eps)
+    if big.any():
+        assert rel_err(np.asarray(step_gpu)[big], np.asarray(step_ref)[big])[0] <= 10 * tol, what
+
+
+def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, fwd_tol=None,
                     bf16_gemm_oracle=None, batch_index=0):
-    """Run one full iteration on the GPU and with the oracle; compare every result."""
+    """Run one full iteration on the GPU and with the oracle; compare every result.
+    `tol` bounds gradients and updates, `fwd_tol` (default: tol) the forward results."""
     from gpu_helpers import GpuRun
     from helpers import tables_as_f32
     tables, state, flat, fstate, batch = make_inputs(cfg, nonzero_state, batch_index)
@@ -54,6 +72,7 @@ def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, t
     run.iteration(sizes, batched=batched)
     F, D, R = cfg.num_fields, cfg.dim, cfg.rows_per_field
     W = cfg.input_width
+    fwd_tol = tol if fwd_tol is None else fwd_tol
     tol_x = 2.0 ** -8 if cfg.gemm_dtype == "bf16" else TOL32   # pooled input is stored in the GEMM operand type
     loss = run.loss.cpu().numpy()
     for k, r in enumerate(res):
@@ -63,7 +82,7 @@ def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, t
             continue
         assert_close(x[:, :W], r.x, tol_x, f"pooled input, shard {k}")
         assert np.all(x[:, W:] == 0)
-        assert abs(loss[k] - r.loss) <= tol * abs(r.loss), f"loss shard {k}: {loss[k]} vs {r.loss}"
+        assert abs(loss[k] - r.loss) <= fwd_tol * abs(r.loss), f"loss shard {k}: {loss[k]} vs {r.loss}"
         assert_close(dense, flat_dense_grad(cfg, r.dW, r.db), tol, f"dense gradient, shard {k}")
         assert_close(dx, r.dx, tol, f"d loss / d pooled, shard {k}")
     assert_close(run.g_dense, flat_dense_grad(cfg, agg.dW, agg.db), tol, "aggregated dense gradient")
@@ -86,8 +105,18 @@ def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, t
         want[u] = upd.rows[f]
         got = new_tables[f * R:(f + 1) * R]
         if cfg.table_dtype == "f32":
-            assert_close(got, want, 1e-6, f"updated table {f}")
-            assert_close(got[u] - t32[f * R + u], upd.rows[f] - t32[f * R + u], tol, f"table step {f}")
+            # End to end the step is compared normwise: from a zero accumulator the step is
+            # lr*g/(|g|+eps), which for the few |g| ~ eps amplifies the rounding error of g by
+            # up to 1/eps.  Element by element the optimizer is held to the tolerance on
+            # identical inputs: the oracle's rule applied to the gradient the GPU aggregated.
+            assert rel_err(got, want)[0] <= tol, f"updated table {f}"
+            G_gpu = run.coalesced[f][3]
+            assert_step_within_bound(got[u] - t32[f * R + u], upd.rows[f] - t32[f * R + u], agg.G[f], cfg, tol,
+                                     f"table step {f}")
+            rule = oracle.adagrad_rowwise if cfg.adagrad_state == "rowwise" else oracle.adagrad_elementwise
+            p1, s1 = rule(t32[f * R + u], state[f * R + u], G_gpu, cfg.lr, cfg.eps)
+            assert_close(got[u] - t32[f * R + u], p1 - t32[f * R + u], TOL32, f"Adagrad rule on the GPU's G, field {f}")
+            assert_close(new_state[f * R + u], s1, TOL32, f"Adagrad accumulator on the GPU's G, field {f}")
         else:
             # the write-back is a rounding decision: both sides round to nearest-even bf16;
             # where the unrounded values sit next to a tie the codes may differ by one ulp
@@ -106,9 +135,13 @@ def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, t
         assert np.array_equal(new_state[f * R:(f + 1) * R][untouched], state[f * R:(f + 1) * R][untouched])
     p_new = run.params.cpu().numpy()
     p_want = flat_layers(cfg, upd.layers)
-    assert_close(p_new, p_want, 1e-6, "updated MLP parameters")
-    assert_close(p_new - flat, p_want - flat, tol, "MLP parameter step")
+    assert rel_err(p_new, p_want)[0] <= tol, "updated MLP parameters"
+    assert_step_within_bound(p_new - flat, p_want - flat, flat_dense_grad(cfg, agg.dW, agg.db), cfg, tol,
+                             "MLP parameter step")
     assert_close(run.pstate.cpu().numpy(), flat_layers(cfg, upd.layer_state), tol, "MLP accumulators")
+    p1, s1 = oracle.adagrad_elementwise(flat, fstate, run.g_dense, cfg.lr, cfg.eps)
+    assert_close(p_new - flat, p1 - flat, TOL32, "Adagrad rule on the GPU's dense gradient")
+    assert_close(run.pstate.cpu().numpy(), s1, TOL32, "dense accumulator on the GPU's gradient")
     return run, agg
 
 
@@ -138,17 +171,52 @@ def test_mid_fp32_multi_tile_long_segments():
     assert max(len(wl.make_batch(MID).field_ids(f)) for f in range(MID.num_fields)) > 2 * 4096
 
 
+# bf16-operand configurations.  The parity oracle takes the configuration's stated precision
+# (GEMM operands rounded to bf16, exact accumulation): which hidden units pass the ReLU is a
+# yes/no decision taken by floating point, so both sides must take it on the same rounded
+# operands.  Against that oracle the bound is the stated 2e-2 (measured: ~3e-3, from
+# accumulation order and one-ulp flips of a rounded activation).  Against the plain float64
+# oracle the forward results stay within 2e-2, but gradients cannot: operands that differ by
+# 2^-9 flip a fraction ~2^-9 of the ReLU decisions, each flip changes that unit's gradient by
+# 100 %, and the normwise error grows like the square root of the flipped fraction per layer
+# (the two *oracles* differ by 5-7 % on these shapes); only a gross-error bound is asserted.
+PLAIN_GRAD_TOL = 0.25
+
+
+def check_against_plain_oracle(cfg):
+    from gpu_helpers import GpuRun
+    from helpers import tables_as_f32
+    tables, state, flat, fstate, batch = make_inputs(cfg)
+    t32 = tables_as_f32(cfg, tables)
+    _, res, agg, _ = oracle_iteration(cfg, t32, state, flat, fstate, batch, cfg.shard_sizes, bf16_gemm=False)
+    run = GpuRun(cfg, tables, flat, state, fstate)
+    run.set_batch(batch)
+    run.iteration(cfg.shard_sizes, batched=True, update=False)
+    loss = run.loss.cpu().numpy()
+    for k, r in enumerate(res):
+        if r.length == 0:
+            continue
+        x, dense, dx = run.shard_out[k]
+        assert_close(x[:, :cfg.input_width], r.x, 2.0 ** -8, f"pooled input, shard {k}")
+        assert abs(loss[k] - r.loss) <= TOLBF * abs(r.loss)
+        assert rel_err(dense, flat_dense_grad(cfg, r.dW, r.db))[0] <= PLAIN_GRAD_TOL
+        assert rel_err(dx, r.dx)[0] <= PLAIN_GRAD_TOL
+    for f in range(cfg.num_fields):
+        u, so, ss, G = run.coalesced[f]
+        assert np.array_equal(u.astype(np.int64), agg.unique_ids[f])
+        assert np.array_equal(so.astype(np.int64), agg.seg_offsets[f])
+        assert rel_err(G, agg.G[f])[0] <= PLAIN_GRAD_TOL
+
+
 def test_mid_bf16_gemm_against_bf16_operand_oracle_and_plain_oracle():
-    # same operand rounding on both sides: differences are accumulation order and rare
-    # one-ulp flips of a rounded activation
-    check_iteration(MID_BF, MID_BF.shard_sizes, tol=3e-3, bf16_gemm_oracle=True)
-    # against the plain float64 oracle: the stated bf16 bound
-    check_iteration(MID_BF, MID_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=False, batched=True)
+    check_iteration(MID_BF, MID_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True)
+    check_against_plain_oracle(MID_BF)
 
 
 def test_rowwise_state_bf16_tables():
-    check_iteration(ROW_BF, ROW_BF.shard_sizes, tol=3e-3, bf16_gemm_oracle=True, nonzero_state=True)
-    check_iteration(ROW_BF, ROW_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=False, batched=True)
+    check_iteration(ROW_BF, ROW_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True, nonzero_state=True)
+    check_iteration(ROW_BF, ROW_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True, batched=True, batch_index=1)
+    check_against_plain_oracle(ROW_BF)
 
 
 def test_batched_and_per_shard_worker_steps_agree():
@@ -199,8 +267,19 @@ def test_dense_aggregate_adam(n, step, weights):
     p1, m1, v1 = oracle.dense_aggregate_adam(p, m, v, grads, w, dc.lr, dc.beta1, dc.beta2, dc.eps, step)
     assert_close(dm.cpu().numpy(), m1, TOL32, "m")
     assert_close(dv.cpu().numpy(), v1, TOL32, "v")
-    assert_close(dp.cpu().numpy(), p1, 1e-6, "p")
-    assert_close(dp.cpu().numpy() - p, p1 - p, TOL32, "Adam step")
+    got = dp.cpu().numpy()
+    assert rel_err(got, p1)[0] <= 1e-6, "p"
+    assert rel_err(got - p, p1 - p)[0] <= TOL32, "Adam step, normwise"
+    if n:
+        # Element by element: the averaged gradient carries fp32 rounding, delta ~ 1e-6*max|g|;
+        # where |g| ~ eps the step lr*m^/(sqrt(v^)+eps) amplifies it, so the bound is the
+        # oracle's own step at g +- delta, plus the tolerance on the step size.
+        g = oracle.weighted_average(grads, w)
+        delta = 1e-6 * np.abs(g).max()
+        hi = oracle.adam_step(p, m, v, g + delta, dc.lr, dc.beta1, dc.beta2, dc.eps, step)[0]
+        lo = oracle.adam_step(p, m, v, g - delta, dc.lr, dc.beta1, dc.beta2, dc.eps, step)[0]
+        bound = np.maximum(np.abs(hi - p1), np.abs(lo - p1)) + TOL32 * np.abs(p1 - p).max()
+        assert np.all(np.abs(got - p1) <= bound), "Adam step outside the bound derived from the oracle"
 
 
 def test_fill_tables_matches_generator():
