@@ -349,7 +349,7 @@ hipError_t launch_sort_pass(const SortPlan& pl, const SortBuffers& sb, int pass,
   if (pl.total_tiles == 0) return hipSuccess;
   const int shift = pass * pl.radix_bits;
   const int32_t* kin = pass == 0 ? sb.ids : sb.key[(pass - 1) & 1];
-  const int32_t* pin = pass == 0 ? nullptr : sb.pay[(pass - 1) & 1];
+  const int32_t* pin = pass == 0 ? sb.pay0 : sb.pay[(pass - 1) & 1];
   dim3 grid(pl.max_tiles, pl.F);
   {
     ProfScope ps(prof, KID_SORT_HIST, s);

@@ -62,6 +62,7 @@ enum KernelId {
   KID_SPARSE_ADAGRAD,
   KID_DENSE_ADAGRAD,
   KID_ADAM,
+  KID_TRANSPOSE,
   KID_COUNT
 };
 
@@ -88,8 +89,10 @@ struct PoolArgs {
   const int32_t* offsets;
   const float* dense;
   void* x;
+  bf16_t* xt;             // optional transposed copy [ldx + 8, ldt] (bf16 activations only)
+  int32_t* lookup_sample; // optional [nnz]: global sample index of every lookup (sort payload)
   int32_t F, D, num_dense, ldx, B, s0, ns;
-  int64_t R;
+  int64_t R, ldt;
   int32_t table_bf16, x_bf16;
 };
 hipError_t launch_pool(const PoolArgs& a, const FieldPtr& fp, hipStream_t s);
@@ -99,17 +102,22 @@ hipError_t launch_fill_tables(void* tables, int bf16, int F, int64_t R, int D, f
 // ----------------------------------------------------------------- gemm.hip
 enum Epilogue { EPI_BIAS_RELU = 0, EPI_RELU_MASK = 1, EPI_PLAIN = 2 };
 
-// C[m, n] = sum_k A(m, k) * B(n, k).  a_kc: A(m,k) = A[m*lda + k], else A[k*lda + m];
-// b_kc: B(n,k) = B[n*ldb + k], else B[k*ldb + n].  With `grouped`, group g (blockIdx.z)
-// contracts over rows [tab.start[k0+g], +tab.len[k0+g]) of A and B (both not *_kc) and
-// writes C + (k0+g)*group_stride.
+// C[m, n] = sum_k A(m, k) * B(n, k).
+// fp32 path: a_kc: A(m,k) = A[m*lda + k], else A[k*lda + m]; b_kc likewise for B; with
+// `grouped`, group g (blockIdx.z) contracts over rows [tab.start[k0+g], +tab.len[k0+g]) of A
+// and B (both not *_kc).
+// bf16 path: both operands have the contraction index contiguous (A[m*lda + k], B[n*ldb + k]);
+// with `grouped`, group g contracts over k in [tab.start[k0+g], +tab.len[k0+g]).
+// Grouped launches write C + (k0+g)*group_stride.  CT, when set, receives the bf16 result
+// transposed: CT[n*ldct + ct_col0 + m].
 struct GemmArgs {
   const void* A;
   const void* B;
   void* C;
+  bf16_t* CT;
   const float* bias;   // EPI_BIAS_RELU: [N]
   const void* mask;    // EPI_RELU_MASK: activations [M, ldmask], C = acc where mask > 0 else 0
-  int64_t lda, ldb, ldc, ldmask;
+  int64_t lda, ldb, ldc, ldct, ct_col0, ldmask;
   int32_t M, N, K;
   int32_t a_kc, b_kc, epi;
   int32_t bf16_in;     // operands (and mask) are bf16, else fp32
@@ -126,6 +134,23 @@ struct CastArgs {  // fp32 [rows, cols] -> bf16 [rows_pad, cols], extra rows zer
 };
 hipError_t launch_cast_bf16(const CastArgs& a, hipStream_t s);
 
+struct TransposeArgs {  // dst[c*ld_dst + r] = src[r*ld_src + c] for up to 8 bf16 matrices
+  int32_t n;
+  const bf16_t* src[ANTDT_MAX_LAYERS];
+  bf16_t* dst[ANTDT_MAX_LAYERS];
+  int32_t rows[ANTDT_MAX_LAYERS], cols[ANTDT_MAX_LAYERS];
+  int64_t ld_src[ANTDT_MAX_LAYERS], ld_dst[ANTDT_MAX_LAYERS];
+  int32_t tile_base[ANTDT_MAX_LAYERS + 1];
+};
+hipError_t launch_transpose_bf16(const TransposeArgs& a, hipStream_t s);
+
+struct OnesRowArgs {    // row `row` of a bf16 matrix [.., ld] = 1, the `zero_rows` rows after it = 0
+  bf16_t* base;
+  int64_t ld;
+  int32_t row, zero_rows;
+};
+hipError_t launch_ones_row(const OnesRowArgs& a, hipStream_t s);
+
 // ----------------------------------------------------------------- head.hip
 struct HeadArgs {
   const void* h;        // [B, ldh] last hidden activation (or the pooled input when there is none)
@@ -136,7 +161,8 @@ struct HeadArgs {
   float* loss_s;        // [B] per-sample loss
   float* dz;            // [B] d(mean shard loss)/dz
   void* dh;             // [B, lddh] gradient w.r.t. h (masked by h > 0 when `relu`), or fp32 dX
-  int64_t ldh, lddh;
+  bf16_t* dht;          // optional transposed bf16 copy [dh_cols, ldt]
+  int64_t ldh, lddh, ldt;
   int32_t width, dh_cols, relu, bf16_h, bf16_dh;
   int32_t k_begin, k_end;
 };
@@ -149,7 +175,8 @@ struct HeadReduceArgs {
   float* grads;         // [K, P] per-shard flat dense gradients
   float* loss_k;        // workspace [K]
   float* loss_out;      // caller's buffer or NULL; element (k - k_begin)
-  int64_t ldh, P, w_off, b_off;
+  const bf16_t* ht;     // optional transposed activation [width, ldt]: selects the coalesced kernel
+  int64_t ldh, ldt, P, w_off, b_off;
   int32_t width, bf16_h, k_begin, k_end;
 };
 hipError_t launch_head_reduce(const HeadReduceArgs& a, const ShardTab& tab, hipStream_t s);
@@ -172,6 +199,7 @@ struct SortPlan {
 struct SortBuffers {
   const int32_t* ids;
   const int32_t* offsets;          // [F][B+1]
+  const int32_t* pay0;             // sample index of every lookup (payload of the first pass)
   int32_t* key[2];
   int32_t* pay[2];
   uint32_t* hist;                  // [total_tiles << radix_bits]

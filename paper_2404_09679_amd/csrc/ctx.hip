@@ -62,7 +62,7 @@ static const char* kKernelNames[KID_COUNT] = {
     "pool",        "gemm_fwd",   "gemm_dgrad",     "gemm_wgrad",  "head",
     "head_reduce", "bias_grad",  "sort_hist",      "sort_scan",   "sort_scatter",
     "seg_heads",   "seg_scan",   "seg_emit",       "seg_reduce",  "seg_reduce_long",
-    "dense_agg",   "sparse_adagrad", "dense_adagrad", "adam"};
+    "dense_agg",   "sparse_adagrad", "dense_adagrad", "adam", "transpose"};
 
 }  // namespace antdt
 
@@ -100,7 +100,12 @@ struct antdt_ctx {
   char* dh[ANTDT_MAX_LAYERS] = {};
   float *z = nullptr, *loss_s = nullptr, *dz = nullptr, *loss_k = nullptr, *dx = nullptr;
   float *shard_grads = nullptr, *g_dense = nullptr, *sample_w = nullptr, *G = nullptr;
-  bf16_t* wb[ANTDT_MAX_LAYERS] = {};
+  bf16_t* wb[ANTDT_MAX_LAYERS] = {};     // bf16 W_l as [in (padded), out]: operand of the data gradient
+  bf16_t* wbt[ANTDT_MAX_LAYERS] = {};    // bf16 W_l^T as [out, in (padded)]: operand of the forward product
+  bf16_t* act_t[ANTDT_MAX_LAYERS] = {};  // transposed activations [width + 8, ldt], row `width` = ones
+  bf16_t* dh_t[ANTDT_MAX_LAYERS] = {};   // transposed pre-activation gradients [width, ldt]
+  int64_t ldt = 0;
+  int32_t* lookup_sample = nullptr;
   int32_t *key[2] = {}, *pay[2] = {}, *tile_heads = nullptr, *ubase = nullptr, *uniq = nullptr;
   int32_t *segoff = nullptr, *long_count = nullptr, *long_list = nullptr;
   uint32_t* hist = nullptr;
@@ -162,11 +167,19 @@ static size_t carve(antdt_ctx* c, char* base) {
   c->dx = (float*)take((size_t)Bm * c->FD * 4);
   c->shard_grads = (float*)take((size_t)K * c->P * 4);
   c->g_dense = (float*)take((size_t)c->P * 4);
-  if (c->act_bf16)
+  if (c->act_bf16) {
     for (int l = 0; l + 1 < c->L; ++l) {
       const int64_t rows = l == 0 ? c->ldx : c->width[l];
       c->wb[l] = (bf16_t*)take((size_t)rows * c->width[l + 1] * 2);
+      c->wbt[l] = (bf16_t*)take((size_t)rows * c->width[l + 1] * 2);
     }
+    for (int l = 0; l < c->L; ++l) {
+      const int64_t rows = (l == 0 ? c->ldx : c->width[l]) + 8;
+      c->act_t[l] = (bf16_t*)take((size_t)rows * c->ldt * 2);
+      if (l > 0) c->dh_t[l] = (bf16_t*)take((size_t)c->width[l] * c->ldt * 2);
+    }
+  }
+  c->lookup_sample = (int32_t*)take((size_t)N * 4);
   for (int i = 0; i < 2; ++i) {
     c->key[i] = (int32_t*)take((size_t)N * 4);
     c->pay[i] = (int32_t*)take((size_t)N * 4);
@@ -220,6 +233,7 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
   c->ldx = (c->in0 + 7) / 8 * 8;
   c->act_bf16 = m.gemm_dtype == ANTDT_BF16;
   c->act_size = c->act_bf16 ? 2 : 4;
+  c->ldt = (m.max_batch + 63) / 64 * 64;
   int64_t off = 0;
   for (int l = 0; l <= c->L; ++l) c->width[l] = m.layer_sizes[l];
   for (int l = 0; l < c->L; ++l) {
@@ -258,6 +272,23 @@ int antdt_workspace_bytes(const antdt_ctx* ctx, size_t* bytes) {
   return ANTDT_OK;
 }
 
+// wbt[l] = transpose of wb[l] for every hidden layer, one launch.
+static int transpose_weights(antdt_ctx* c, hipStream_t s) {
+  if (!c->act_bf16 || c->L < 2) return ANTDT_OK;
+  TransposeArgs t;
+  memset(&t, 0, sizeof(t));
+  for (int l = 0; l + 1 < c->L; ++l) {
+    const int rows = l == 0 ? c->ldx : c->width[l], cols = c->width[l + 1];
+    t.src[l] = c->wb[l]; t.dst[l] = c->wbt[l];
+    t.rows[l] = rows; t.cols[l] = cols; t.ld_src[l] = cols; t.ld_dst[l] = rows;
+    t.tile_base[l + 1] = t.tile_base[l] + ((rows + 63) / 64) * ((cols + 63) / 64);
+  }
+  t.n = c->L - 1;
+  ProfScope ps(prof_of(c), KID_TRANSPOSE, s);
+  HIP_TRY(c, launch_transpose_bf16(t, s));
+  return ANTDT_OK;
+}
+
 static int refresh_bf16_weights(antdt_ctx* c, hipStream_t s) {
   if (!c->act_bf16) return ANTDT_OK;
   for (int l = 0; l + 1 < c->L; ++l) {
@@ -268,7 +299,17 @@ static int refresh_bf16_weights(antdt_ctx* c, hipStream_t s) {
     a.n_dst = (int64_t)(l == 0 ? c->ldx : c->width[l]) * c->width[l + 1];
     HIP_TRY(c, launch_cast_bf16(a, s));
   }
-  return ANTDT_OK;
+  // constant rows of the transposed activations: a row of ones below the last feature row
+  // (it turns the bias gradient into one more row of the weight-gradient product), zeros after
+  for (int l = 0; l < c->L; ++l) {
+    OnesRowArgs o;
+    o.base = c->act_t[l];
+    o.ld = c->ldt;
+    o.row = c->width[l];
+    o.zero_rows = (l == 0 ? c->ldx : c->width[l]) + 8 - c->width[l] - 1;
+    HIP_TRY(c, launch_ones_row(o, s));
+  }
+  return transpose_weights(c, s);
 }
 
 int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params, float* mlp_state,
@@ -408,6 +449,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     a.F = m.num_fields; a.D = m.dim; a.num_dense = m.num_dense; a.ldx = c->ldx; a.B = (int32_t)c->B;
     a.s0 = (int32_t)s0; a.ns = (int32_t)ns; a.R = m.rows_per_field;
     a.table_bf16 = m.table_dtype == ANTDT_BF16; a.x_bf16 = c->act_bf16;
+    a.xt = c->act_bf16 ? c->act_t[0] : nullptr; a.ldt = c->ldt; a.lookup_sample = c->lookup_sample;
     ProfScope ps(pr, KID_POOL, s);
     HIP_TRY(c, launch_pool(a, c->fp, s));
   }
@@ -420,11 +462,17 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = act(l) + s0 * ld(l) * es; g.lda = ld(l); g.a_kc = 1;
-    g.B = weight(l); g.ldb = c->width[l + 1]; g.b_kc = 0;
     g.C = c->h[l + 1] + s0 * c->width[l + 1] * es; g.ldc = c->width[l + 1];
     g.bias = c->params + c->b_off[l];
     g.M = (int32_t)ns; g.N = c->width[l + 1];
-    g.K = (l == 0 && c->act_bf16) ? c->ldx : c->width[l];
+    if (c->act_bf16) {  // B = W_l^T [out, in padded]; the result also goes to the transposed copy
+      g.K = (int32_t)ld(l);
+      g.B = c->wbt[l]; g.ldb = ld(l); g.b_kc = 1;
+      g.CT = c->act_t[l + 1]; g.ldct = c->ldt; g.ct_col0 = s0;
+    } else {
+      g.K = c->width[l];
+      g.B = c->params + c->w_off[l]; g.ldb = c->width[l + 1]; g.b_kc = 0;
+    }
     g.epi = EPI_BIAS_RELU; g.bf16_in = c->act_bf16; g.bf16_out = c->act_bf16;
     ProfScope ps(pr, KID_GEMM_FWD, s);
     HIP_TRY(c, launch_gemm(g, tab, s));
@@ -451,26 +499,58 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     r.h = act(L - 1); r.ldh = ld(L - 1); r.width = c->width[L - 1]; r.bf16_h = c->act_bf16;
     r.dz = c->dz; r.loss_s = c->loss_s; r.grads = c->shard_grads; r.loss_k = c->loss_k; r.loss_out = loss_out;
     r.P = c->P; r.w_off = c->w_off[L - 1]; r.b_off = c->b_off[L - 1]; r.k_begin = k0; r.k_end = k1;
-    ProfScope ps(pr, KID_HEAD_REDUCE, s);
-    HIP_TRY(c, launch_head_reduce(r, tab, s));
+    if (c->act_bf16 && L > 1) {
+      r.ht = c->act_t[L - 1];
+      r.ldt = c->ldt;
+    }
+    {
+      ProfScope ps(pr, KID_HEAD_REDUCE, s);
+      HIP_TRY(c, launch_head_reduce(r, tab, s));
+    }
+    if (c->act_bf16 && L > 1) {  // the weight-gradient product wants dh^T
+      TransposeArgs t;
+      memset(&t, 0, sizeof(t));
+      t.n = 1;
+      t.src[0] = (const bf16_t*)c->dh[L - 1] + s0 * c->width[L - 1];
+      t.dst[0] = c->dh_t[L - 1] + s0;
+      t.rows[0] = (int32_t)ns; t.cols[0] = c->width[L - 1];
+      t.ld_src[0] = c->width[L - 1]; t.ld_dst[0] = c->ldt;
+      t.tile_base[1] = (int32_t)((ns + 63) / 64) * ((c->width[L - 1] + 63) / 64);
+      ProfScope ps(pr, KID_TRANSPOSE, s);
+      HIP_TRY(c, launch_transpose_bf16(t, s));
+    }
   }
   for (int l = L - 2; l >= 0; --l) {
-    {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
+    if (c->act_bf16) {
+      // [dW_l ; db_l][k] = [act_l ; 1]^T dh_{l+1} over the shard's samples: both operands are the
+      // transposed copies (sample index contiguous); the ones row yields the bias gradient,
+      // which sits right behind W_l in the flat layout.
       GemmArgs g;
       memset(&g, 0, sizeof(g));
-      g.A = act(l); g.lda = ld(l); g.a_kc = 0;
-      g.B = c->dh[l + 1]; g.ldb = c->width[l + 1]; g.b_kc = 0;
+      g.A = c->act_t[l]; g.lda = c->ldt;
+      g.B = c->dh_t[l + 1]; g.ldb = c->ldt;
       g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
-      g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
-      g.epi = EPI_PLAIN; g.bf16_in = c->act_bf16; g.bf16_out = 0;
+      g.M = c->width[l] + 1; g.N = c->width[l + 1]; g.K = 0;
+      g.epi = EPI_PLAIN; g.bf16_in = 1; g.bf16_out = 0;
       g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->P;
       ProfScope ps(pr, KID_GEMM_WGRAD, s);
       HIP_TRY(c, launch_gemm(g, tab, s));
-    }
-    {
+    } else {
+      {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.A = act(l); g.lda = ld(l); g.a_kc = 0;
+        g.B = c->dh[l + 1]; g.ldb = c->width[l + 1]; g.b_kc = 0;
+        g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
+        g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
+        g.epi = EPI_PLAIN; g.bf16_in = 0; g.bf16_out = 0;
+        g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->P;
+        ProfScope ps(pr, KID_GEMM_WGRAD, s);
+        HIP_TRY(c, launch_gemm(g, tab, s));
+      }
       BiasGradArgs b;
       memset(&b, 0, sizeof(b));
-      b.dh = c->dh[l + 1]; b.lddh = c->width[l + 1]; b.width = c->width[l + 1]; b.bf16_dh = c->act_bf16;
+      b.dh = c->dh[l + 1]; b.lddh = c->width[l + 1]; b.width = c->width[l + 1]; b.bf16_dh = 0;
       b.grads = c->shard_grads; b.P = c->P; b.b_off = c->b_off[l]; b.k_begin = k0; b.k_end = k1;
       ProfScope ps(pr, KID_BIAS_GRAD, s);
       HIP_TRY(c, launch_bias_grad(b, tab, s));
@@ -486,6 +566,9 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
         g.C = c->dh[l] + s0 * c->width[l] * es; g.ldc = c->width[l]; g.N = c->width[l];
         g.mask = c->h[l] + s0 * c->width[l] * es; g.ldmask = c->width[l];
         g.epi = EPI_RELU_MASK; g.bf16_out = c->act_bf16;
+        if (c->act_bf16) {
+          g.CT = c->dh_t[l]; g.ldct = c->ldt; g.ct_col0 = s0;
+        }
       } else {
         g.C = c->dx + s0 * c->FD; g.ldc = c->FD; g.N = c->FD;
         g.epi = EPI_PLAIN; g.bf16_out = 0;
@@ -540,6 +623,7 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
   sb.ids = c->ids; sb.offsets = c->offsets;
   sb.key[0] = c->key[0]; sb.key[1] = c->key[1]; sb.pay[0] = c->pay[0]; sb.pay[1] = c->pay[1];
   sb.hist = c->hist;
+  sb.pay0 = c->lookup_sample;
   for (int p = 0; p < pl.passes; ++p) HIP_TRY(c, launch_sort_pass(pl, sb, p, c->fp, c->tb, pr, s));
   c->sorted_buf = (pl.passes - 1) & 1;
 
@@ -591,6 +675,10 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
       }
     ProfScope ps(pr, KID_DENSE_ADAGRAD, s);
     HIP_TRY(c, launch_dense_adagrad(a, s));
+  }
+  {
+    const int rc = transpose_weights(c, s);
+    if (rc) return rc;
   }
   c->stage = ST_BATCH;
   memset(c->stepped, 0, sizeof(c->stepped));

@@ -20,31 +20,134 @@ template <> struct Vec16<bf16_t> {
   }
 };
 
-// One wavefront per (sample, field) bag.  The 64 lanes are split into 64/LPR
-// groups of LPR = D*sizeof(T)/16 lanes; every group streams one table row per
-// step with 16-byte loads (a whole row is one contiguous, fully used request),
-// so up to 64/LPR rows of the bag are in flight at once.  Partial sums are
-// combined with a butterfly over the groups and group 0 writes the pooled row.
-// The "field" index F stands for the dense-feature columns of the sample.
+template <typename OT, int N> __device__ __forceinline__ void store_row(OT* dst, const float* v);
+template <> __device__ __forceinline__ void store_row<float, 4>(float* dst, const float* v) {
+  *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ __forceinline__ void store_row<float, 8>(float* dst, const float* v) {
+  reinterpret_cast<float4*>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);
+  reinterpret_cast<float4*>(dst)[1] = make_float4(v[4], v[5], v[6], v[7]);
+}
+template <> __device__ __forceinline__ void store_row<bf16_t, 4>(bf16_t* dst, const float* v) {
+  *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16),
+                                              (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16));
+}
+template <> __device__ __forceinline__ void store_row<bf16_t, 8>(bf16_t* dst, const float* v) {
+  *reinterpret_cast<uint4*>(dst) = make_uint4((uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16),
+                                              (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16),
+                                              (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16),
+                                              (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16));
+}
+
+// Dense-feature columns of 64 samples: copied behind the pooled embeddings (and into the
+// transposed copy), the padding columns of the row are zeroed.
+template <typename OT>
+__device__ __forceinline__ void dense_columns(const PoolArgs& a, int sl0) {
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  if (sl0 + tx >= a.ns) return;
+  const int64_t s = a.s0 + sl0 + tx;
+  const int FD = a.F * a.D;
+  OT* xrow = reinterpret_cast<OT*>(a.x) + s * a.ldx + FD;
+  for (int c = ty; c < a.ldx - FD; c += 4) {
+    const float v = c < a.num_dense ? a.dense[s * a.num_dense + c] : 0.0f;
+    xrow[c] = from_f32<OT>(v);
+    if (a.xt && c < a.num_dense) a.xt[(int64_t)(FD + c) * a.ldt + s] = f2bf(v);
+  }
+}
+
+// Gather and sum-pool.  A block owns 64 consecutive samples of one field; a group of
+// LPR = D*sizeof(T)/16 lanes owns one bag, so a wavefront works on 64/LPR bags at once.
+// The group fetches LPR ids with one coalesced load, hands them round with lane
+// shuffles and issues the LPR row loads (16 bytes per lane, one whole row per group)
+// back to back before adding them, which keeps 64 rows in flight per wavefront.  The
+// pooled rows are written to X and, through an LDS tile, to the transposed copy that the
+// weight-gradient GEMM reads.  Every lookup's sample index is recorded for the sort.
+template <typename TT, typename OT, int LPR>
+__global__ __launch_bounds__(256) void pool_tile_kernel(PoolArgs a, FieldPtr fp) {
+  constexpr int EV = Vec16<TT>::N;
+  constexpr int G = 256 / LPR;       // bags per round
+  constexpr int ROUNDS = 64 / G;
+  constexpr int TP = 130;            // tile pitch (odd number of dwords: conflict-free column reads)
+  __shared__ bf16_t tile[64 * TP];
+  const int f = blockIdx.y, sl0 = blockIdx.x * 64;
+  if (f == a.F) {
+    dense_columns<OT>(a, sl0);
+    return;
+  }
+  const int g = threadIdx.x / LPR, c = threadIdx.x % LPR;
+  const int gl = (threadIdx.x & 63) - c;  // first lane of this group inside the wavefront
+  const int32_t* ids = a.ids + fp.p[f];
+  const TT* tab = reinterpret_cast<const TT*>(a.tables) + (int64_t)f * a.R * a.D + c * EV;
+  const bool use_tile = a.xt != nullptr && a.D <= 128;
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int ls = r * G + g;
+    const bool valid = sl0 + ls < a.ns;
+    const int64_t s = a.s0 + sl0 + ls;
+    int begin = 0, end = 0;
+    if (valid) {
+      const int32_t* off = a.offsets + (int64_t)f * (a.B + 1) + s;
+      begin = off[0];
+      end = off[1];
+    }
+    float acc[EV];
+#pragma unroll
+    for (int e = 0; e < EV; ++e) acc[e] = 0.0f;
+    for (int jb = begin; jb < end; jb += LPR) {
+      const int my_j = jb + c;
+      int my_id = 0;
+      if (my_j < end) {
+        my_id = ids[my_j];
+        if (a.lookup_sample) a.lookup_sample[fp.p[f] + my_j] = (int32_t)s;
+      }
+      Vec16<TT> v[LPR];
+#pragma unroll
+      for (int q = 0; q < LPR; ++q) {
+        const int64_t row = min(max((int64_t)__shfl(my_id, gl + q, 64), (int64_t)0), a.R - 1);
+        if (jb + q < end) v[q].v = *reinterpret_cast<const decltype(v[q].v)*>(tab + row * a.D);
+      }
+#pragma unroll
+      for (int q = 0; q < LPR; ++q)
+        if (jb + q < end) {
+#pragma unroll
+          for (int e = 0; e < EV; ++e) acc[e] += v[q].get(e);
+        }
+    }
+    if (valid) {
+      store_row<OT, EV>(reinterpret_cast<OT*>(a.x) + s * a.ldx + f * a.D + c * EV, acc);
+      if (a.xt) {
+        if (use_tile) {
+#pragma unroll
+          for (int e = 0; e < EV; ++e) tile[ls * TP + c * EV + e] = f2bf(acc[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < EV; ++e) a.xt[(int64_t)(f * a.D + c * EV + e) * a.ldt + s] = f2bf(acc[e]);
+        }
+      }
+    }
+  }
+  if (use_tile) {
+    __syncthreads();
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    if (sl0 + tx < a.ns) {
+      bf16_t* dst = a.xt + (int64_t)f * a.D * a.ldt + a.s0 + sl0 + tx;
+      for (int d = ty; d < a.D; d += 4) dst[(int64_t)d * a.ldt] = tile[tx * TP + d];
+    }
+  }
+}
+
+// Fallback for other row sizes: one wavefront per (sample, field) bag, 64/LPR rows in
+// flight, partial sums combined with a butterfly over the lane groups.
 template <typename TT, typename OT>
 __global__ __launch_bounds__(256) void pool_kernel(PoolArgs a, FieldPtr fp) {
   constexpr int EV = Vec16<TT>::N;
   const int lane = threadIdx.x & 63;
   const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int nf = a.F + 1;
-  const int64_t sl = item / nf;
+  const int64_t sl = item / a.F;
   if (sl >= a.ns) return;
-  const int f = (int)(item - sl * nf);
+  const int f = (int)(item - sl * a.F);
   const int64_t s = a.s0 + sl;
   OT* xrow = reinterpret_cast<OT*>(a.x) + s * a.ldx;
-  if (f == a.F) {
-    const int ncol = a.ldx - a.F * a.D;  // dense features, then zero padding
-    for (int c = lane; c < ncol; c += 64) {
-      float v = c < a.num_dense ? a.dense[s * a.num_dense + c] : 0.0f;
-      xrow[a.F * a.D + c] = from_f32<OT>(v);
-    }
-    return;
-  }
   const int lpr = a.D / EV;  // lanes per row, power of two
   const int rpi = 64 / lpr;  // rows in flight
   const int sub = lane / lpr;
@@ -53,6 +156,8 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolArgs a, FieldPtr fp) {
   const int begin = off[0], end = off[1];
   const int32_t* ids = a.ids + fp.p[f];
   const TT* tab = reinterpret_cast<const TT*>(a.tables) + (int64_t)f * a.R * a.D + c * EV;
+  if (a.lookup_sample)
+    for (int j = begin + lane; j < end; j += 64) a.lookup_sample[fp.p[f] + j] = (int32_t)s;
   float acc[EV];
 #pragma unroll
   for (int e = 0; e < EV; ++e) acc[e] = 0.0f;
@@ -68,22 +173,41 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolArgs a, FieldPtr fp) {
     for (int e = 0; e < EV; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
   }
   if (sub == 0) {
-    OT* dst = xrow + f * a.D + c * EV;
+    store_row<OT, EV>(xrow + f * a.D + c * EV, acc);
+    if (a.xt) {
 #pragma unroll
-    for (int e = 0; e < EV; ++e) dst[e] = from_f32<OT>(acc[e]);
+      for (int e = 0; e < EV; ++e) a.xt[(int64_t)(f * a.D + c * EV + e) * a.ldt + s] = f2bf(acc[e]);
+    }
+  }
+}
+
+template <typename OT>
+__global__ __launch_bounds__(256) void pool_dense_kernel(PoolArgs a) {
+  dense_columns<OT>(a, blockIdx.x * 64);
+}
+
+template <typename TT, typename OT>
+static void launch_pool_typed(const PoolArgs& a, const FieldPtr& fp, hipStream_t s) {
+  const int lpr = a.D / Vec16<TT>::N;
+  dim3 grid((a.ns + 63) / 64, a.F + 1), block(256);
+  if (lpr == 4) hipLaunchKernelGGL((pool_tile_kernel<TT, OT, 4>), grid, block, 0, s, a, fp);
+  else if (lpr == 8) hipLaunchKernelGGL((pool_tile_kernel<TT, OT, 8>), grid, block, 0, s, a, fp);
+  else if (lpr == 16) hipLaunchKernelGGL((pool_tile_kernel<TT, OT, 16>), grid, block, 0, s, a, fp);
+  else {
+    const int64_t items = (int64_t)a.ns * a.F;
+    hipLaunchKernelGGL((pool_kernel<TT, OT>), dim3((unsigned)((items + 3) / 4)), block, 0, s, a, fp);
+    hipLaunchKernelGGL((pool_dense_kernel<OT>), dim3((a.ns + 63) / 64), block, 0, s, a);
   }
 }
 
 hipError_t launch_pool(const PoolArgs& a, const FieldPtr& fp, hipStream_t s) {
   if (a.ns <= 0) return hipSuccess;
-  const int64_t items = (int64_t)a.ns * (a.F + 1);
-  dim3 grid((unsigned)((items + 3) / 4)), block(256);
   if (a.table_bf16) {
-    if (a.x_bf16) hipLaunchKernelGGL((pool_kernel<bf16_t, bf16_t>), grid, block, 0, s, a, fp);
-    else hipLaunchKernelGGL((pool_kernel<bf16_t, float>), grid, block, 0, s, a, fp);
+    if (a.x_bf16) launch_pool_typed<bf16_t, bf16_t>(a, fp, s);
+    else launch_pool_typed<bf16_t, float>(a, fp, s);
   } else {
-    if (a.x_bf16) hipLaunchKernelGGL((pool_kernel<float, bf16_t>), grid, block, 0, s, a, fp);
-    else hipLaunchKernelGGL((pool_kernel<float, float>), grid, block, 0, s, a, fp);
+    if (a.x_bf16) launch_pool_typed<float, bf16_t>(a, fp, s);
+    else launch_pool_typed<float, float>(a, fp, s);
   }
   return hipGetLastError();
 }

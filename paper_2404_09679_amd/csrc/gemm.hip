@@ -1,185 +1,277 @@
 // MLP matrix products of the worker step (forward, data gradient, weight gradient).
 //   bf16 operands / fp32 accumulate: LDS-tiled kernel on the gfx950 matrix cores
-//   (v_mfma_f32_16x16x32_bf16, 64-wide wavefronts);
+//   (v_mfma_f32_32x32x16_bf16, 64-wide wavefronts; measured on MI355X it sustains ~2.2 PFLOP/s
+//   where the 16x16x32 form stays near 1.3), every operand stored with the contraction
+//   index contiguous so that an MFMA fragment is one 16-byte LDS read;
 //   fp32: a plain LDS-tiled FMA kernel (small models, exactness checks).
 #include "common.h"
 
 namespace antdt {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int BK = 32;          // contraction depth of one LDS tile = one MFMA
-constexpr int PITCH_KC = 40;    // bf16 elements per row of a [rows][BK] tile (80 B, 16-byte aligned)
-constexpr int PITCH_NK = 132;   // bf16 elements per row of a [BK][cols<=128] tile (264 B, 8-byte aligned)
+constexpr int BK = 64;      // contraction depth of one LDS tile (four MFMA k-steps)
+constexpr int PITCH = 72;   // bf16 elements per LDS row: 144 B puts the 16 rows of a fragment read
+                            // on 16 distinct 16-byte bank groups
 
-__device__ __forceinline__ float epilogue_mask(const GemmArgs& p, int64_t m, int n) {
-  if (p.bf16_in) return bf2f(reinterpret_cast<const bf16_t*>(p.mask)[m * p.ldmask + n]);
-  return reinterpret_cast<const float*>(p.mask)[m * p.ldmask + n];
+__device__ __forceinline__ float epilogue_value(const GemmArgs& p, int64_t m, int n, float acc) {
+  if (p.epi == EPI_BIAS_RELU) return fmaxf(acc + p.bias[n], 0.0f);
+  if (p.epi == EPI_RELU_MASK) {
+    const float h = p.bf16_in ? bf2f(reinterpret_cast<const bf16_t*>(p.mask)[m * p.ldmask + n])
+                              : reinterpret_cast<const float*>(p.mask)[m * p.ldmask + n];
+    return h > 0.0f ? acc : 0.0f;
+  }
+  return acc;
 }
 
-__device__ __forceinline__ void epilogue_store(const GemmArgs& p, void* Cbase, int64_t m, int n, float acc) {
-  float v = acc;
-  if (p.epi == EPI_BIAS_RELU) v = fmaxf(acc + p.bias[n], 0.0f);
-  else if (p.epi == EPI_RELU_MASK) v = epilogue_mask(p, m, n) > 0.0f ? acc : 0.0f;
-  if (p.bf16_out) reinterpret_cast<bf16_t*>(Cbase)[m * p.ldc + n] = f2bf(v);
-  else reinterpret_cast<float*>(Cbase)[m * p.ldc + n] = v;
+// Branch-free: zero the elements of an 8-element bf16 vector starting at contraction index
+// k that fall outside [ks, ke); `all` is 0 or ~0 and clears the whole vector.
+__device__ __forceinline__ uint4 clip_k(uint4 v, int k, int ks, int ke, uint32_t all) {
+  const int lo = ks - k, hi = ke - k;  // element e survives iff lo <= e < hi
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const uint32_t m0 = (2 * e >= lo && 2 * e < hi) ? 0x0000FFFFu : 0u;
+    const uint32_t m1 = (2 * e + 1 >= lo && 2 * e + 1 < hi) ? 0xFFFF0000u : 0u;
+    w[e] &= (m0 | m1) & all;
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// Block tile (32*TM) x (32*TN), 4 wavefronts in a 2x2 arrangement, each owning
-// TM x TN MFMA tiles of 16x16.  Operand tiles go global -> registers -> LDS
-// (double buffered, one barrier per K step).  An operand whose contraction
-// index is contiguous in memory is kept as [row][k] and read back with one
-// 16-byte LDS load per fragment; the other kind is kept as [k][col] and its
-// fragment is gathered with eight 2-byte LDS loads.
-template <int TM, int TN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs p, ShardTab tab) {
-  constexpr int BM = 32 * TM, BN = 32 * TN;
-  constexpr int A_ELEMS = A_KC ? BM * PITCH_KC : BK * PITCH_NK;
-  constexpr int B_ELEMS = B_KC ? BN * PITCH_KC : BK * PITCH_NK;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (A_ELEMS + B_ELEMS)];
+// Two packed bf16 values, each kept where the matching mask value is positive.
+__device__ __forceinline__ uint32_t relu_mask2(uint32_t v, uint32_t mk) {
+  const uint32_t lo = ((mk & 0x8000u) == 0 && (mk & 0x7FFFu) != 0) ? 0x0000FFFFu : 0u;
+  const uint32_t hi = ((mk & 0x80000000u) == 0 && (mk & 0x7FFF0000u) != 0) ? 0xFFFF0000u : 0u;
+  return v & (lo | hi);
+}
+
+// C[m, n] = sum_{k in [ks, ke)} A[m*lda + k] * B[n*ldb + k].
+// Block tile (64*TM) x (64*TN), four wavefronts 2x2, each TM x TN MFMA tiles of 32x32.
+// Global -> registers -> LDS with the next tile's loads in flight during the MFMAs.
+// Blocks are numbered so that the blocks sharing an A row-panel run on the same XCD (L2).
+template <int TM, int TN, bool GROUPED>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab, int tiles_m, int tiles_n) {
+  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int VA = BM * BK / 8 / 256, VB = BN * BK / 8 / 256;  // 16-byte vectors per thread
+  __shared__ __attribute__((aligned(16))) bf16_t lds[(BM + BN) * PITCH];
+  bf16_t* la = lds;
+  bf16_t* lb = lds + BM * PITCH;
 
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
   char* C = reinterpret_cast<char*>(p.C);
-  int K = p.K;
-  if (p.grouped) {
+  int ks = 0, ke = p.K;
+  if (GROUPED) {
     const int k = p.k0 + blockIdx.z;
-    const int64_t r0 = tab.start[k];
-    K = tab.len[k];
-    A += r0 * p.lda;
-    B += r0 * p.ldb;
+    ks = tab.start[k];
+    ke = ks + tab.len[k];
     C += (int64_t)k * p.group_stride * (p.bf16_out ? 2 : 4);
   }
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  int pid = blockIdx.x;
+  const int nblk = tiles_m * tiles_n;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  const int fr = lane & 15, fg = lane >> 4;
+  const int fr = lane & 31, fg = lane >> 5;
 
-  constexpr int VA = BM * BK / 8 / 256;  // 16-byte vectors per thread for the A tile
-  constexpr int VB = BN * BK / 8 / 256;
-  uint4 ra[VA], rb[VB];
-
-  auto load_tile = [&](int k0) {
+  // Two register stages: while tile kt is multiplied out of LDS, tiles kt+1 and kt+2 are in
+  // flight from L2/HBM (one block per compute unit leaves no other wavefront to hide that
+  // latency behind).
+  uint4 ra0[VA], rb0[VB], ra1[VA], rb1[VB];
+  const int kfirst = ks & ~7;
+  // Loads are unconditional (addresses clamped into the operand) so that all of a tile's
+  // loads are issued back to back; rows / contraction slots outside the problem are zeroed
+  // when the tile is moved to LDS.
+  const int klast = (ke - 1) & ~7;
+  auto load_tile = [&](int kt, uint4 (&ra)[VA], uint4 (&rb)[VB]) {
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
       const int v = tid + i * 256;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (A_KC) {
-        const int row = v >> 2, kc = (v & 3) * 8;
-        if (m0 + row < p.M && k0 + kc < K) val = *reinterpret_cast<const uint4*>(A + (int64_t)(m0 + row) * p.lda + k0 + kc);
-      } else {
-        constexpr int CPR = BM / 8;  // vectors per k row
-        const int kk = v / CPR, cc = (v % CPR) * 8;
-        if (k0 + kk < K && m0 + cc < p.M) val = *reinterpret_cast<const uint4*>(A + (int64_t)(k0 + kk) * p.lda + m0 + cc);
-      }
-      ra[i] = val;
+      const int row = min(m0 + (v >> 3), p.M - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
+      ra[i] = *reinterpret_cast<const uint4*>(A + (int64_t)row * p.lda + k);
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
       const int v = tid + i * 256;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (B_KC) {
-        const int row = v >> 2, kc = (v & 3) * 8;
-        if (n0 + row < p.N && k0 + kc < K) val = *reinterpret_cast<const uint4*>(B + (int64_t)(n0 + row) * p.ldb + k0 + kc);
-      } else {
-        constexpr int CPR = BN / 8;
-        const int kk = v / CPR, cc = (v % CPR) * 8;
-        if (k0 + kk < K && n0 + cc < p.N) val = *reinterpret_cast<const uint4*>(B + (int64_t)(k0 + kk) * p.ldb + n0 + cc);
-      }
-      rb[i] = val;
+      const int row = min(n0 + (v >> 3), p.N - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
+      rb[i] = *reinterpret_cast<const uint4*>(B + (int64_t)row * p.ldb + k);
     }
   };
-  auto store_tile = [&](int buf) {
-    bf16_t* la = lds + buf * (A_ELEMS + B_ELEMS);
-    bf16_t* lb = la + A_ELEMS;
+  // straight-line code only: a branch here makes the compiler wait for every outstanding load
+  auto fix = [&](uint4 val, bool row_ok, int k) -> uint4 {
+    const uint32_t all = (row_ok && k < ke) ? 0xFFFFFFFFu : 0u;
+    if (GROUPED) return clip_k(val, k, ks, ke, all);
+    return make_uint4(val.x & all, val.y & all, val.z & all, val.w & all);
+  };
+  auto store_tile = [&](int kt, const uint4 (&ra)[VA], const uint4 (&rb)[VB]) {
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
       const int v = tid + i * 256;
-      if (A_KC) {
-        const int row = v >> 2, kc = (v & 3) * 8;
-        *reinterpret_cast<uint4*>(la + row * PITCH_KC + kc) = ra[i];
-      } else {
-        constexpr int CPR = BM / 8;
-        const int kk = v / CPR, cc = (v % CPR) * 8;
-        uint2* d = reinterpret_cast<uint2*>(la + kk * PITCH_NK + cc);
-        d[0] = make_uint2(ra[i].x, ra[i].y);
-        d[1] = make_uint2(ra[i].z, ra[i].w);
-      }
+      const uint4 val = fix(ra[i], m0 + (v >> 3) < p.M, kfirst + kt * BK + (v & 7) * 8);
+      *reinterpret_cast<uint4*>(la + (v >> 3) * PITCH + (v & 7) * 8) = val;
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
       const int v = tid + i * 256;
-      if (B_KC) {
-        const int row = v >> 2, kc = (v & 3) * 8;
-        *reinterpret_cast<uint4*>(lb + row * PITCH_KC + kc) = rb[i];
-      } else {
-        constexpr int CPR = BN / 8;
-        const int kk = v / CPR, cc = (v % CPR) * 8;
-        uint2* d = reinterpret_cast<uint2*>(lb + kk * PITCH_NK + cc);
-        d[0] = make_uint2(rb[i].x, rb[i].y);
-        d[1] = make_uint2(rb[i].z, rb[i].w);
-      }
+      const uint4 val = fix(rb[i], n0 + (v >> 3) < p.N, kfirst + kt * BK + (v & 7) * 8);
+      *reinterpret_cast<uint4*>(lb + (v >> 3) * PITCH + (v & 7) * 8) = val;
     }
-  };
-  // Fragment of a 16-row MFMA tile starting at tile row `r0`: lane (fr, fg) supplies the
-  // 8 contraction slots fg*8 .. fg*8+7 of row r0 + fr.
-  auto frag = [&](const bf16_t* base, bool kc, int r0) -> bf16x8 {
-    union { uint4 u; bf16x8 v; uint16_t h[8]; } x;
-    if (kc) {
-      x.u = *reinterpret_cast<const uint4*>(base + (r0 + fr) * PITCH_KC + fg * 8);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x.h[e] = base[(fg * 8 + e) * PITCH_NK + r0 + fr];
-    }
-    return x.v;
   };
 
-  f32x4 acc[TM][TN];
+  f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  const int nk = (K + BK - 1) / BK;
+  auto multiply = [&]() {
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      // lane (fr, fg) supplies contraction slots fg*8 .. fg*8+7 of row fr of each 32-row tile
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(la + (wr * (BM / 2) + i * 32 + fr) * PITCH + kk + fg * 8);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(lb + (wc * (BN / 2) + j * 32 + fr) * PITCH + kk + fg * 8);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  // Slabs are processed in pairs and every load is issued unconditionally (addresses past
+  // the end are clamped, the data is zeroed by `fix`): with conditional loads the compiler
+  // cannot count outstanding loads and drains them all before each LDS store.
+  const int nk = ke > kfirst ? (ke - kfirst + BK - 1) / BK : 0;
   if (nk > 0) {
-    load_tile(0);
-    store_tile(0);
+    load_tile(0, ra0, rb0);
+    load_tile(1, ra1, rb1);
   }
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_tile((kt + 1) * BK);
-    const bf16_t* la = lds + buf * (A_ELEMS + B_ELEMS);
-    const bf16_t* lb = la + A_ELEMS;
-    bf16x8 af[TM], bfr[TN];
+  for (int kt = 0; kt < nk; kt += 2) {
+    store_tile(kt, ra0, rb0);
+    __syncthreads();
+    load_tile(kt + 2, ra0, rb0);
+    multiply();
+    __syncthreads();
+    store_tile(kt + 1, ra1, rb1);
+    __syncthreads();
+    load_tile(kt + 3, ra1, rb1);
+    multiply();
+    __syncthreads();
+  }
+
+  // Epilogue.  In the D fragment lane (fr, fg) holds column fr and rows 8*(v/4) + 4*fg + v%4
+  // (v = 0..15) of each 32x32 tile, which would mean 2-byte scattered stores.  Each wavefront instead stages its
+  // tile in its own slice of the (now free) LDS and writes it out row by row in 16-byte
+  // pieces; the ReLU mask is read the same way; the transposed copy is read back column-wise.
+  constexpr int WM = 32 * TM, WN = 32 * TN;
+  const int mw = m0 + wr * WM, nw = n0 + wc * WN;
+  if (p.bf16_out) {
+    constexpr int SP = WN + 8;
+    bf16_t* st = lds + wave * (WM * SP);
+    float bias[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[i] = frag(la, A_KC, wr * (BM / 2) + i * 16);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[j] = frag(lb, B_KC, wc * (BN / 2) + j * 16);
+    for (int j = 0; j < TN; ++j) {
+      const int n = nw + j * 32 + fr;
+      bias[j] = (p.epi == EPI_BIAS_RELU && n < p.N) ? p.bias[n] : 0.0f;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    if (kt + 1 < nk) store_tile(buf ^ 1);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float v = acc[i][j][e];
+          if (p.epi == EPI_BIAS_RELU) v = fmaxf(v + bias[j], 0.0f);
+          st[(i * 32 + 8 * (e >> 2) + 4 * fg + (e & 3)) * SP + j * 32 + fr] = f2bf(v);
+        }
     __syncthreads();
-  }
-
-  // D fragment: lane (fr, fg) holds column fr and rows fg*4 .. fg*4+3 of each 16x16 tile.
+    constexpr int CPR = WN / 8;    // 16-byte pieces per row
+    constexpr int RPI = 64 / CPR;  // rows per wavefront instruction
+    const int rr = lane / CPR, cc = (lane % CPR) * 8;
+    bf16_t* Cb = reinterpret_cast<bf16_t*>(C);
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wc * (BN / 2) + j * 16 + fr;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int m = m0 + wr * (BM / 2) + i * 16 + fg * 4 + v;
-        if (m < p.M && n < p.N) epilogue_store(p, C, m, n, acc[i][j][v]);
+    for (int r0 = 0; r0 < WM; r0 += RPI) {
+      const int r = r0 + rr, m = mw + r, n = nw + cc;
+      if (m < p.M && n < p.N) {
+        uint4 val = *reinterpret_cast<const uint4*>(st + r * SP + cc);
+        if (p.epi == EPI_RELU_MASK) {
+          const uint4 mk = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.mask) + (int64_t)m * p.ldmask + n);
+          val = make_uint4(relu_mask2(val.x, mk.x), relu_mask2(val.y, mk.y), relu_mask2(val.z, mk.z), relu_mask2(val.w, mk.w));
+          if (p.CT) *reinterpret_cast<uint4*>(st + r * SP + cc) = val;
+        }
+        *reinterpret_cast<uint4*>(Cb + (int64_t)m * p.ldc + n) = val;
       }
     }
+    if (p.CT) {
+      __syncthreads();
+      constexpr int CPI = WN < 64 ? WN : 64;  // columns per wavefront instruction
+      constexpr int HV = 64 / CPI;
+      const int col = lane % CPI, hv = lane / CPI;
+      const int n = nw + col;
+      for (int mc = hv; mc < WM / 8; mc += HV) {
+        const int mb = mw + mc * 8;
+        if (n < p.N && mb < p.M) {
+          bf16_t h[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) h[e] = st[(mc * 8 + e) * SP + col];
+          bf16_t* dst = p.CT + (int64_t)n * p.ldct + p.ct_col0 + mb;
+          if (mb + 7 < p.M && ((p.ct_col0 + mb) & 7) == 0) {
+            *reinterpret_cast<uint4*>(dst) = make_uint4((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16),
+                                                        (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (mb + e < p.M) dst[e] = h[e];
+          }
+        }
+      }
+    }
+  } else {
+    constexpr int SPF = WN + 4;
+    constexpr int ROWS = 32;  // rows staged per pass: one MFMA tile row
+    float* stf = reinterpret_cast<float*>(lds) + wave * (ROWS * SPF);
+    constexpr int CPR = WN / 4;
+    constexpr int RPI = 64 / CPR;
+    const int rr = lane / CPR, cc = (lane % CPR) * 4;
+    float* Cf = reinterpret_cast<float*>(C);
+#pragma unroll
+    for (int pass = 0; pass < WM / ROWS; ++pass) {
+      if (pass) __syncthreads();
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          stf[(8 * (e >> 2) + 4 * fg + (e & 3)) * SPF + j * 32 + fr] = acc[pass][j][e];
+      __syncthreads();
+#pragma unroll
+      for (int r0 = 0; r0 < ROWS; r0 += RPI) {
+        const int r = r0 + rr, m = mw + pass * ROWS + r, n = nw + cc;
+        if (m < p.M && n < p.N) {
+          const float4 val = *reinterpret_cast<const float4*>(stf + r * SPF + cc);
+          float* dst = Cf + (int64_t)m * p.ldc + n;
+          if (n + 3 < p.N && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+            *reinterpret_cast<float4*>(dst) = val;
+          } else {
+            dst[0] = val.x;
+            if (n + 1 < p.N) dst[1] = val.y;
+            if (n + 2 < p.N) dst[2] = val.z;
+            if (n + 3 < p.N) dst[3] = val.w;
+          }
+        }
+      }
+    }
+  }
 }
 
 // fp32 tiled FMA kernel with arbitrary operand orientation: 64x64 block tile, 4x4 per thread.
@@ -234,7 +326,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs p, ShardTab tab)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-      if (m < p.M && n < p.N) epilogue_store(p, C, m, n, acc[i][j]);
+      if (m < p.M && n < p.N) reinterpret_cast<float*>(C)[(int64_t)m * p.ldc + n] = epilogue_value(p, m, n, acc[i][j]);
     }
 }
 
@@ -244,13 +336,37 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(CastArgs a) {
     a.dst[i] = i < a.n_src ? f2bf(a.src[i]) : (bf16_t)0;
 }
 
+// 64x64 bf16 tiles transposed through LDS; one launch covers several matrices.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(TransposeArgs a) {
+  __shared__ bf16_t tile[64][66];
+  int mi = 0;
+  while (mi + 1 < a.n && (int)blockIdx.x >= a.tile_base[mi + 1]) ++mi;
+  const int t = blockIdx.x - a.tile_base[mi];
+  const int tc = (a.cols[mi] + 63) / 64;
+  const int r0 = (t / tc) * 64, c0 = (t % tc) * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4)
+    tile[r][tx] = (r0 + r < a.rows[mi] && c0 + tx < a.cols[mi]) ? a.src[mi][(int64_t)(r0 + r) * a.ld_src[mi] + c0 + tx]
+                                                              : (bf16_t)0;
+  __syncthreads();
+  for (int cidx = ty; cidx < 64; cidx += 4)
+    if (c0 + cidx < a.cols[mi] && r0 + tx < a.rows[mi])
+      a.dst[mi][(int64_t)(c0 + cidx) * a.ld_dst[mi] + r0 + tx] = tile[tx][cidx];
+}
+
+__global__ __launch_bounds__(256) void ones_row_kernel(OnesRowArgs a) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.ld) return;
+  a.base[(int64_t)a.row * a.ld + i] = 0x3F80;  // 1.0
+  for (int r = 1; r <= a.zero_rows; ++r) a.base[(int64_t)(a.row + r) * a.ld + i] = 0;
+}
+
 template <int TM, int TN>
-void launch_mfma_variant(const GemmArgs& a, const ShardTab& tab, dim3 grid, hipStream_t s) {
-  dim3 block(256);
-  if (a.a_kc && a.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, true, true>), grid, block, 0, s, a, tab);
-  else if (a.a_kc && !a.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, true, false>), grid, block, 0, s, a, tab);
-  else if (!a.a_kc && !a.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, false, false>), grid, block, 0, s, a, tab);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, false, true>), grid, block, 0, s, a, tab);
+void launch_bf16_variant(const GemmArgs& a, const ShardTab& tab, int groups, hipStream_t s) {
+  const int tiles_m = (a.M + 64 * TM - 1) / (64 * TM), tiles_n = (a.N + 64 * TN - 1) / (64 * TN);
+  dim3 grid(tiles_m * tiles_n, 1, groups);
+  if (a.grouped) hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, true>), grid, dim3(256), 0, s, a, tab, tiles_m, tiles_n);
+  else hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, false>), grid, dim3(256), 0, s, a, tab, tiles_m, tiles_n);
 }
 
 }  // namespace
@@ -264,15 +380,11 @@ hipError_t launch_gemm(const GemmArgs& a, const ShardTab& tab, hipStream_t s) {
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, s, a, tab);
     return hipGetLastError();
   }
-  // Large tiles when they still give the 256 compute units enough blocks, else 64x64.
-  const int64_t big = (int64_t)((a.N + 127) / 128) * ((a.M + 127) / 128) * groups;
-  if (big >= 192) {
-    dim3 grid((a.N + 127) / 128, (a.M + 127) / 128, groups);
-    launch_mfma_variant<4, 4>(a, tab, grid, s);
-  } else {
-    dim3 grid((a.N + 63) / 64, (a.M + 63) / 64, groups);
-    launch_mfma_variant<2, 2>(a, tab, grid, s);
-  }
+  // The largest tile that still gives the 256 compute units about one block each.
+  auto blocks = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * groups; };
+  if (blocks(128, 128) >= 200) launch_bf16_variant<2, 2>(a, tab, groups, s);
+  else if (blocks(128, 64) >= 200) launch_bf16_variant<2, 1>(a, tab, groups, s);
+  else launch_bf16_variant<1, 1>(a, tab, groups, s);
   return hipGetLastError();
 }
 
@@ -281,6 +393,17 @@ hipError_t launch_cast_bf16(const CastArgs& a, hipStream_t s) {
   int64_t blocks = (a.n_dst + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_bf16(const TransposeArgs& a, hipStream_t s) {
+  if (a.n <= 0 || a.tile_base[a.n] <= 0) return hipSuccess;
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3(a.tile_base[a.n]), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_ones_row(const OnesRowArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(ones_row_kernel, dim3((unsigned)((a.ld + 255) / 256)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -89,6 +89,40 @@ __global__ __launch_bounds__(256) void head_reduce_kernel(HeadReduceArgs a, Shar
   }
 }
 
+// The same reductions from the transposed activation hT[j][s]: one wavefront per (j, shard)
+// reads a contiguous run of samples; wavefront `width` of a shard does db and the loss.
+__global__ __launch_bounds__(256) void head_reduce_t_kernel(HeadReduceArgs a, ShardTab tab) {
+  const int k = a.k_begin + blockIdx.y;
+  const int64_t s0 = tab.start[k];
+  const int n = tab.len[k];
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  float* g = a.grads + (int64_t)k * a.P;
+  if (j < a.width) {
+    const bf16_t* h = a.ht + (int64_t)j * a.ldt + s0;
+    float acc = 0.0f;
+#pragma unroll 4
+    for (int s = lane; s < n; s += 64) acc = fmaf(bf2f(h[s]), a.dz[s0 + s], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) g[a.w_off + j] = acc;
+  } else if (j == a.width) {
+    float sdz = 0.0f, sl = 0.0f;
+#pragma unroll 4
+    for (int s = lane; s < n; s += 64) {
+      sdz += a.dz[s0 + s];
+      sl += a.loss_s[s0 + s];
+    }
+    sdz = wave_sum(sdz);
+    sl = wave_sum(sl);
+    if (lane == 0) {
+      g[a.b_off] = sdz;
+      const float lk = n > 0 ? sl / (float)n : 0.0f;
+      a.loss_k[k] = lk;
+      if (a.loss_out) a.loss_out[k - a.k_begin] = lk;
+    }
+  }
+}
+
 // db[k][o] = sum over the samples of shard k of dh[s, o].
 template <typename TD>
 __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs a, ShardTab tab) {
@@ -132,6 +166,10 @@ hipError_t launch_head(const HeadArgs& a, const ShardTab& tab, hipStream_t s) {
 }
 
 hipError_t launch_head_reduce(const HeadReduceArgs& a, const ShardTab& tab, hipStream_t s) {
+  if (a.ht) {
+    hipLaunchKernelGGL(head_reduce_t_kernel, dim3((a.width + 1 + 3) / 4, a.k_end - a.k_begin), dim3(256), 0, s, a, tab);
+    return hipGetLastError();
+  }
   dim3 grid((a.width + 63) / 64, a.k_end - a.k_begin), block(256);
   if (a.bf16_h) hipLaunchKernelGGL(head_reduce_kernel<bf16_t>, grid, block, 0, s, a, tab);
   else hipLaunchKernelGGL(head_reduce_kernel<float>, grid, block, 0, s, a, tab);
