@@ -3,7 +3,8 @@
 // sort of (row id, sample index) pairs, detection of the runs of equal ids
 // (unique ids + segment offsets), and the weighted segmented reduction
 //   G[u, :] = sum over the run of w(sample) * dX[sample, field slice].
-// No floating-point atomics are used, so the sums are bitwise repeatable.
+// No floating-point atomics are used, so the sums are bitwise repeatable.  The reduction can
+// apply the row-sparse Adagrad step of each row at once (Section II: "update the parameters").
 #include "common.h"
 
 namespace antdt {
@@ -21,7 +22,10 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
 }
 
 // ----------------------------------------------------------------- sort
-// Digit histogram of one tile: hist[(tile_base[f] << rb) + digit * T_f + tile].
+// Histogram layout: hist[(tile_base[f] + tile) << rb | digit] (digits of a tile contiguous);
+// digit_base[f << rb | digit] = number of the field's keys with a smaller digit.
+
+// Digit histogram of one tile.
 __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const int32_t* keys, uint32_t* hist,
                                                                  FieldPtr fp, TileBase tb, int shift, int rb) {
   __shared__ uint32_t h[MAX_BINS];
@@ -29,35 +33,55 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const int32_t* 
   const int tiles = tb.t[f + 1] - tb.t[f];
   if (t >= tiles) return;
   const int nb = 1 << rb;
-  for (int d = threadIdx.x; d < nb; d += SORT_THREADS) h[d] = 0;
-  __syncthreads();
   const int64_t base = fp.p[f];
   const int nnz = (int)(fp.p[f + 1] - base);
+  int32_t k[SORT_ITEMS];
+#pragma unroll
+  for (int i = 0; i < SORT_ITEMS; ++i) {  // all loads first (clamped), so that they overlap
+    const int pos = min(t * SORT_TILE + i * SORT_THREADS + (int)threadIdx.x, nnz - 1);
+    k[i] = keys[base + pos];
+  }
+  for (int d = threadIdx.x; d < nb; d += SORT_THREADS) h[d] = 0;
+  __syncthreads();
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {
     const int pos = t * SORT_TILE + i * SORT_THREADS + threadIdx.x;
-    if (pos < nnz) atomicAdd(&h[(keys[base + pos] >> shift) & (nb - 1)], 1u);
+    if (pos < nnz) atomicAdd(&h[((uint32_t)k[i] >> shift) & (nb - 1)], 1u);
   }
   __syncthreads();
-  uint32_t* out = hist + ((int64_t)tb.t[f] << rb);
-  for (int d = threadIdx.x; d < nb; d += SORT_THREADS) out[(int64_t)d * tiles + t] = h[d];
+  uint32_t* out = hist + ((int64_t)(tb.t[f] + t) << rb);
+  for (int d = threadIdx.x; d < nb; d += SORT_THREADS) out[d] = h[d];
 }
 
-// Exclusive prefix sum, in place, over the (digit-major, tile-minor) histogram of one field.
-__global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t* hist, TileBase tb, int rb) {
-  __shared__ uint32_t wsum[16];
+// One block per field, one thread per digit: the counts of a digit are replaced by their
+// exclusive prefix over the tiles, and the digit totals by their exclusive prefix over digits.
+__global__ __launch_bounds__(MAX_BINS) void sort_scan_kernel(uint32_t* hist, uint32_t* digit_base, TileBase tb, int rb) {
+  __shared__ uint32_t wsum[MAX_BINS / 64];
   const int f = blockIdx.x;
   const int tiles = tb.t[f + 1] - tb.t[f];
-  const int n = tiles << rb;
-  if (n == 0) return;
-  uint32_t* h = hist + ((int64_t)tb.t[f] << rb);
-  const int chunk = (n + 1023) / 1024;
-  const int lo = min(n, (int)threadIdx.x * chunk), hi = min(n, lo + chunk);
-  uint32_t sum = 0;
-  for (int i = lo; i < hi; ++i) sum += h[i];
-  // block-wide exclusive scan of the per-thread sums
+  const int nb = 1 << rb;
+  const int d = threadIdx.x;
+  uint32_t run = 0;
+  if (d < nb) {
+    uint32_t* h = hist + ((int64_t)tb.t[f] << rb) + d;
+    int t = 0;
+    for (; t + 3 < tiles; t += 4) {  // four independent loads in flight
+      const uint32_t c0 = h[(int64_t)t << rb], c1 = h[(int64_t)(t + 1) << rb];
+      const uint32_t c2 = h[(int64_t)(t + 2) << rb], c3 = h[(int64_t)(t + 3) << rb];
+      h[(int64_t)t << rb] = run;
+      h[(int64_t)(t + 1) << rb] = run + c0;
+      h[(int64_t)(t + 2) << rb] = run + c0 + c1;
+      h[(int64_t)(t + 3) << rb] = run + c0 + c1 + c2;
+      run += c0 + c1 + c2 + c3;
+    }
+    for (; t < tiles; ++t) {
+      const uint32_t c = h[(int64_t)t << rb];
+      h[(int64_t)t << rb] = run;
+      run += c;
+    }
+  }
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  uint32_t incl = sum;
+  uint32_t incl = run;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
     const uint32_t v = __shfl_up(incl, o, 64);
@@ -67,39 +91,39 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t* hist, TileBas
   __syncthreads();
   uint32_t wbase = 0;
   for (int i = 0; i < w; ++i) wbase += wsum[i];
-  uint32_t run = wbase + incl - sum;
-  for (int i = lo; i < hi; ++i) {
-    const uint32_t c = h[i];
-    h[i] = run;
-    run += c;
-  }
+  if (d < nb) digit_base[((int64_t)f << rb) + d] = wbase + incl - run;
 }
 
 // Stable scatter of one tile.  Wave w owns the contiguous 512-key slice w of the tile and
 // walks it in 8 rounds of 64 keys; lanes holding equal digits find each other with one
 // ballot per digit bit, the per-wave running count of the digit lives in LDS.
 __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
-    const int32_t* keys_in, const int32_t* pay_in, const int32_t* offsets, int32_t* keys_out,
-    int32_t* pay_out, const uint32_t* hist, FieldPtr fp, TileBase tb, int shift, int rb, int B) {
+    const int32_t* keys_in, const int32_t* pay_in, int32_t* keys_out, int32_t* pay_out, const uint32_t* hist,
+    const uint32_t* digit_base, FieldPtr fp, TileBase tb, int shift, int rb) {
   __shared__ uint32_t cnt[SORT_WAVES][MAX_BINS];
   const int f = blockIdx.y, t = blockIdx.x;
   const int tiles = tb.t[f + 1] - tb.t[f];
   if (t >= tiles) return;
   const int nb = 1 << rb;
-  for (int d = threadIdx.x; d < SORT_WAVES * MAX_BINS; d += SORT_THREADS) (&cnt[0][0])[d] = 0;
-  __syncthreads();
   const int64_t base = fp.p[f];
   const int nnz = (int)(fp.p[f + 1] - base);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int32_t key[SORT_ITEMS], pay[SORT_ITEMS];
+#pragma unroll
+  for (int i = 0; i < SORT_ITEMS; ++i) {  // all loads first (clamped), so that they overlap
+    const int pos = min(t * SORT_TILE + w * (64 * SORT_ITEMS) + i * 64 + lane, nnz - 1);
+    key[i] = keys_in[base + pos];
+    pay[i] = pay_in[base + pos];
+  }
+  for (int d = threadIdx.x; d < SORT_WAVES * nb; d += SORT_THREADS) cnt[d >> rb][d & (nb - 1)] = 0;
+  __syncthreads();
   const uint64_t lt = lanemask_lt();
   volatile uint32_t* cw = cnt[w];
-  int32_t key[SORT_ITEMS];
   uint32_t rank[SORT_ITEMS];
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {
     const int pos = t * SORT_TILE + w * (64 * SORT_ITEMS) + i * 64 + lane;
     const bool valid = pos < nnz;
-    key[i] = valid ? keys_in[base + pos] : 0;
     const uint32_t d = ((uint32_t)key[i] >> shift) & (nb - 1);
     uint64_t m = __ballot(valid);
     for (int b = 0; b < rb; ++b) {
@@ -125,29 +149,20 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     }
   }
   __syncthreads();
-  const uint32_t* hb = hist + ((int64_t)tb.t[f] << rb);
-  const int32_t* off = offsets + (int64_t)f * (B + 1);
+  const uint32_t* hb = hist + ((int64_t)(tb.t[f] + t) << rb);
+  const uint32_t* db = digit_base + ((int64_t)f << rb);
+  uint32_t dst[SORT_ITEMS];
+#pragma unroll
+  for (int i = 0; i < SORT_ITEMS; ++i) {
+    const uint32_t d = ((uint32_t)key[i] >> shift) & (nb - 1);
+    dst[i] = db[d] + hb[d] + cnt[w][d] + rank[i];
+  }
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {
     const int pos = t * SORT_TILE + w * (64 * SORT_ITEMS) + i * 64 + lane;
-    if (pos < nnz) {
-      const uint32_t d = ((uint32_t)key[i] >> shift) & (nb - 1);
-      const uint32_t dst = hb[(int64_t)d * tiles + t] + cnt[w][d] + rank[i];
-      int32_t pay;
-      if (pay_in) {
-        pay = pay_in[base + pos];
-      } else {  // first pass: the sample whose bag holds lookup `pos`
-        int lo = 0, hi = B;
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (off[mid] <= pos) lo = mid; else hi = mid;
-        }
-        pay = lo;
-      }
-      if (dst < (uint32_t)nnz) {
-        keys_out[base + dst] = key[i];
-        pay_out[base + dst] = pay;
-      }
+    if (pos < nnz && dst[i] < (uint32_t)nnz) {
+      keys_out[base + dst[i]] = key[i];
+      pay_out[base + dst[i]] = pay[i];
     }
   }
 }
@@ -213,7 +228,9 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(SegArgs a, FieldPtr fp, 
   }
   if (threadIdx.x == 0) {
     a.tile_heads[n] = total;
-    a.long_count[0] = 0;
+    a.counters[0] = 0;
+    a.counters[1] = 0;
+    a.segabs[total] = (int32_t)fp.p[a.F];
   }
   __threadfence_block();
   __syncthreads();
@@ -254,79 +271,159 @@ __global__ __launch_bounds__(SORT_THREADS) void seg_emit_kernel(SegArgs a, Field
   for (int i = 0; i < SORT_ITEMS; ++i)
     if (flags & (1u << i)) {
       a.uniq[rank] = key[p0 + i];
+      a.ufield[rank] = f;
+      a.segabs[rank] = (int32_t)fp.p[f] + p0 + i;
       a.segoff[rank + f] = p0 + i;
       ++rank;
     }
 }
 
-__device__ __forceinline__ int field_of_unique(const int32_t* ubase, int F, int u) {
-  int lo = 0, hi = F;  // ubase[lo] <= u < ubase[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (ubase[mid] <= u) lo = mid; else hi = mid;
+// ------------------------------------------------- weighted run sums (+ update)
+struct Row4 {
+  float v[4];
+};
+
+// g += w(sample) * dX[sample, field slice] over sorted entries [b, e) taken with stride `step`,
+// four entries in flight.
+__device__ __forceinline__ void accumulate_run(const SegArgs& a, const float* dxcol, int b, int e, int step, Row4& g) {
+  int i = b;
+  for (; i + 3 * step < e; i += 4 * step) {
+    int s[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) s[q] = min(max(a.pay[i + q * step], 0), a.B - 1);
+    float w[4];
+    float4 x[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      w[q] = a.sample_w[s[q]];
+      x[q] = *reinterpret_cast<const float4*>(dxcol + (int64_t)s[q] * a.lddx);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      g.v[0] = fmaf(w[q], x[q].x, g.v[0]);
+      g.v[1] = fmaf(w[q], x[q].y, g.v[1]);
+      g.v[2] = fmaf(w[q], x[q].z, g.v[2]);
+      g.v[3] = fmaf(w[q], x[q].w, g.v[3]);
+    }
   }
-  return lo;
+  for (; i < e; i += step) {
+    const int s = min(max(a.pay[i], 0), a.B - 1);
+    const float w = a.sample_w[s];
+    const float4 x = *reinterpret_cast<const float4*>(dxcol + (int64_t)s * a.lddx);
+    g.v[0] = fmaf(w, x.x, g.v[0]);
+    g.v[1] = fmaf(w, x.y, g.v[1]);
+    g.v[2] = fmaf(w, x.z, g.v[2]);
+    g.v[3] = fmaf(w, x.w, g.v[3]);
+  }
 }
 
-// One group of D/4 lanes per run; runs longer than the threshold are queued for the block kernel.
-__global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a, FieldPtr fp) {
+// Row-sparse Adagrad of one table row by its lane group (lane c owns columns 4c .. 4c+3):
+//   element-wise: S += g^2;                 p -= lr * g / (sqrt(S) + eps)
+//   row-wise:     S[r] += mean_d g[r,d]^2;  p -= lr * g / (sqrt(S[r]) + eps)
+// bf16 tables are written back round-to-nearest-even.
+template <typename TT, bool ROWWISE>
+__device__ __forceinline__ void adagrad_row(const SegArgs& a, int64_t row, int c, int lps, const Row4& g,
+                                            const float (&p0)[4], const float4& s0, float srow0) {
+  float den[4], p[4];
+  if (ROWWISE) {
+    float sq = (g.v[0] * g.v[0] + g.v[1] * g.v[1]) + (g.v[2] * g.v[2] + g.v[3] * g.v[3]);
+    for (int o = 1; o < lps; o <<= 1) sq += __shfl_xor(sq, o, 64);
+    const float s1 = srow0 + sq / (float)a.D;
+    if (c == 0) a.state[row] = s1;
+    den[0] = den[1] = den[2] = den[3] = sqrtf(s1) + a.eps;
+  } else {
+    float4 sv = s0;
+    sv.x = fmaf(g.v[0], g.v[0], sv.x);
+    sv.y = fmaf(g.v[1], g.v[1], sv.y);
+    sv.z = fmaf(g.v[2], g.v[2], sv.z);
+    sv.w = fmaf(g.v[3], g.v[3], sv.w);
+    *reinterpret_cast<float4*>(a.state + row * a.D + c * 4) = sv;
+    den[0] = sqrtf(sv.x) + a.eps; den[1] = sqrtf(sv.y) + a.eps;
+    den[2] = sqrtf(sv.z) + a.eps; den[3] = sqrtf(sv.w) + a.eps;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) p[e] = p0[e] - a.lr * g.v[e] / den[e];
+  TT* prow = reinterpret_cast<TT*>(a.tables) + row * a.D + c * 4;
+  if (sizeof(TT) == 4) {
+    *reinterpret_cast<float4*>(prow) = make_float4(p[0], p[1], p[2], p[3]);
+  } else {
+    *reinterpret_cast<uint2*>(prow) = make_uint2((uint32_t)f2bf(p[0]) | ((uint32_t)f2bf(p[1]) << 16),
+                                                 (uint32_t)f2bf(p[2]) | ((uint32_t)f2bf(p[3]) << 16));
+  }
+}
+
+template <typename TT, bool ROWWISE>
+__device__ __forceinline__ void load_row(const SegArgs& a, int64_t row, int c, float (&p0)[4], float4& s0, float& srow0) {
+  const TT* prow = reinterpret_cast<const TT*>(a.tables) + row * a.D + c * 4;
+  if (sizeof(TT) == 4) {
+    const float4 v = *reinterpret_cast<const float4*>(prow);
+    p0[0] = v.x; p0[1] = v.y; p0[2] = v.z; p0[3] = v.w;
+  } else {
+    const uint2 v = *reinterpret_cast<const uint2*>(prow);
+    p0[0] = __uint_as_float(v.x << 16); p0[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    p0[2] = __uint_as_float(v.y << 16); p0[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  }
+  if (ROWWISE) srow0 = a.state[row];
+  else s0 = *reinterpret_cast<const float4*>(a.state + row * a.D + c * 4);
+}
+
+// One group of D/4 lanes per run.  Short runs are summed in sorted (= sample) order and, when
+// `UPDATE`, the Adagrad step of the row is applied at once (the coalesced gradient never
+// goes to memory); otherwise the sum is written to G.  Runs longer than the threshold are
+// cut into chunks that are queued for the block kernel below.
+template <typename TT, bool ROWWISE, bool UPDATE>
+__global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a) {
   const int lps = a.D >> 2;
   const int U = a.ubase[a.F];
   const int groups_per_block = 256 / lps;
   const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
   for (int64_t u = (int64_t)blockIdx.x * groups_per_block + g; u < U; u += (int64_t)gridDim.x * groups_per_block) {
-    const int f = field_of_unique(a.ubase, a.F, (int)u);
-    const int b = a.segoff[u + f], e = a.segoff[u + f + 1];
+    const int b = a.segabs[u], e = a.segabs[u + 1];
+    const int f = a.ufield[u];
+    const int64_t row = (int64_t)f * a.R + min(max(a.uniq[u], 0), (int)(a.R - 1));
     if (e - b > a.long_threshold) {
       if (c == 0) {
-        const int slot = atomicAdd(a.long_count, 1);
-        if (slot < a.long_cap) a.long_list[slot] = (int)u;
+        const int nch = (e - b + a.chunk - 1) / a.chunk;
+        const int slot = atomicAdd(&a.counters[0], 1);
+        const int base = atomicAdd(&a.counters[1], nch);
+        if (slot < a.long_cap && base + nch <= a.item_cap) {
+          a.long_seg[slot * 3 + 0] = (int)u;
+          a.long_seg[slot * 3 + 1] = base;
+          a.long_seg[slot * 3 + 2] = nch;
+          for (int q = 0; q < nch; ++q) {
+            a.items[(base + q) * 2 + 0] = (int)u;
+            a.items[(base + q) * 2 + 1] = q;
+          }
+        }
       }
       continue;
     }
-    const int32_t* pay = a.pay + fp.p[f];
-    const float* dx = a.dx + f * a.D + c * 4;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-    for (int i = b; i < e; ++i) {
-      const int s = min(max(pay[i], 0), a.B - 1);
-      const float w = a.sample_w[s];
-      const float4 v = *reinterpret_cast<const float4*>(dx + (int64_t)s * a.lddx);
-      acc.x = fmaf(w, v.x, acc.x);
-      acc.y = fmaf(w, v.y, acc.y);
-      acc.z = fmaf(w, v.z, acc.z);
-      acc.w = fmaf(w, v.w, acc.w);
-    }
-    *reinterpret_cast<float4*>(a.G + u * a.D + c * 4) = acc;
+    float p0[4] = {0.f, 0.f, 0.f, 0.f};
+    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float srow0 = 0.f;
+    if (UPDATE) load_row<TT, ROWWISE>(a, row, c, p0, s0, srow0);
+    Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
+    accumulate_run(a, a.dx + f * a.D + c * 4, b, e, 1, gsum);
+    if (UPDATE) adagrad_row<TT, ROWWISE>(a, row, c, lps, gsum, p0, s0, srow0);
+    else *reinterpret_cast<float4*>(a.G + u * a.D + c * 4) = make_float4(gsum.v[0], gsum.v[1], gsum.v[2], gsum.v[3]);
   }
 }
 
-// One block per long run: the lane groups stride over the run, then their partial sums are
-// added in group order.
-__global__ __launch_bounds__(256) void seg_reduce_long_kernel(SegArgs a, FieldPtr fp) {
+// One block per chunk of a long run: the lane groups stride over the chunk, then their
+// partial sums are added in group order (fixed order: repeatable bit for bit).
+__global__ __launch_bounds__(256) void seg_chunk_kernel(SegArgs a) {
   __shared__ float4 red[256];
   const int lps = a.D >> 2;
   const int ngroups = 256 / lps;
   const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
-  const int count = min(a.long_count[0], a.long_cap);
+  const int count = min(a.counters[1], a.item_cap);
   for (int idx = blockIdx.x; idx < count; idx += gridDim.x) {
-    const int u = a.long_list[idx];
-    const int f = field_of_unique(a.ubase, a.F, u);
-    const int b = a.segoff[u + f], e = a.segoff[u + f + 1];
-    const int32_t* pay = a.pay + fp.p[f];
-    const float* dx = a.dx + f * a.D + c * 4;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-    for (int i = b + g; i < e; i += ngroups) {
-      const int s = min(max(pay[i], 0), a.B - 1);
-      const float w = a.sample_w[s];
-      const float4 v = *reinterpret_cast<const float4*>(dx + (int64_t)s * a.lddx);
-      acc.x = fmaf(w, v.x, acc.x);
-      acc.y = fmaf(w, v.y, acc.y);
-      acc.z = fmaf(w, v.z, acc.z);
-      acc.w = fmaf(w, v.w, acc.w);
-    }
-    red[threadIdx.x] = acc;
+    const int u = a.items[idx * 2], q = a.items[idx * 2 + 1];
+    const int b = a.segabs[u] + q * a.chunk, e = min(a.segabs[u + 1], b + a.chunk);
+    const int f = a.ufield[u];
+    Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
+    accumulate_run(a, a.dx + f * a.D + c * 4, b + g, e, ngroups, gsum);
+    red[threadIdx.x] = make_float4(gsum.v[0], gsum.v[1], gsum.v[2], gsum.v[3]);
     __syncthreads();
     for (int half = ngroups >> 1; half > 0; half >>= 1) {
       if (g < half) {
@@ -337,8 +434,46 @@ __global__ __launch_bounds__(256) void seg_reduce_long_kernel(SegArgs a, FieldPt
       }
       __syncthreads();
     }
-    if (g == 0) *reinterpret_cast<float4*>(a.G + (int64_t)u * a.D + c * 4) = red[c];
+    if (g == 0) *reinterpret_cast<float4*>(a.partial + (int64_t)idx * a.D + c * 4) = red[c];
     __syncthreads();
+  }
+}
+
+// One lane group per long run: add its chunk sums in chunk order, then update or store.
+template <typename TT, bool ROWWISE, bool UPDATE>
+__global__ __launch_bounds__(256) void seg_finish_kernel(SegArgs a) {
+  const int lps = a.D >> 2;
+  const int groups_per_block = 256 / lps;
+  const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
+  const int count = min(a.counters[0], a.long_cap);
+  for (int idx = blockIdx.x * groups_per_block + g; idx < count; idx += gridDim.x * groups_per_block) {
+    const int u = a.long_seg[idx * 3], base = a.long_seg[idx * 3 + 1], nch = a.long_seg[idx * 3 + 2];
+    const int f = a.ufield[u];
+    const int64_t row = (int64_t)f * a.R + min(max(a.uniq[u], 0), (int)(a.R - 1));
+    float p0[4] = {0.f, 0.f, 0.f, 0.f};
+    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float srow0 = 0.f;
+    if (UPDATE) load_row<TT, ROWWISE>(a, row, c, p0, s0, srow0);
+    Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
+    for (int q = 0; q < nch; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(a.partial + (int64_t)(base + q) * a.D + c * 4);
+      gsum.v[0] += v.x; gsum.v[1] += v.y; gsum.v[2] += v.z; gsum.v[3] += v.w;
+    }
+    if (UPDATE) adagrad_row<TT, ROWWISE>(a, row, c, lps, gsum, p0, s0, srow0);
+    else *reinterpret_cast<float4*>(a.G + (int64_t)u * a.D + c * 4) = make_float4(gsum.v[0], gsum.v[1], gsum.v[2], gsum.v[3]);
+  }
+}
+
+template <typename TT, bool ROWWISE, bool UPDATE>
+void launch_reduce_variant(const SegArgs& a, unsigned blocks, Profiler* prof, hipStream_t s) {
+  {
+    ProfScope ps(prof, UPDATE ? KID_SPARSE_ADAGRAD : KID_SEG_REDUCE, s);
+    hipLaunchKernelGGL((seg_reduce_kernel<TT, ROWWISE, UPDATE>), dim3(blocks), dim3(256), 0, s, a);
+  }
+  {
+    ProfScope ps(prof, KID_SEG_REDUCE_LONG, s);
+    hipLaunchKernelGGL(seg_chunk_kernel, dim3(2048), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((seg_finish_kernel<TT, ROWWISE, UPDATE>), dim3(64), dim3(256), 0, s, a);
   }
 }
 
@@ -357,12 +492,12 @@ hipError_t launch_sort_pass(const SortPlan& pl, const SortBuffers& sb, int pass,
   }
   {
     ProfScope ps(prof, KID_SORT_SCAN, s);
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(pl.F), dim3(1024), 0, s, sb.hist, tb, pl.radix_bits);
+    hipLaunchKernelGGL(sort_scan_kernel, dim3(pl.F), dim3(MAX_BINS), 0, s, sb.hist, sb.digit_base, tb, pl.radix_bits);
   }
   {
     ProfScope ps(prof, KID_SORT_SCATTER, s);
-    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(SORT_THREADS), 0, s, kin, pin, sb.offsets,
-                       sb.key[pass & 1], sb.pay[pass & 1], sb.hist, fp, tb, shift, pl.radix_bits, pl.B);
+    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(SORT_THREADS), 0, s, kin, pin, sb.key[pass & 1],
+                       sb.pay[pass & 1], sb.hist, sb.digit_base, fp, tb, shift, pl.radix_bits);
   }
   return hipGetLastError();
 }
@@ -385,19 +520,31 @@ hipError_t launch_segments(const SegArgs& a, const FieldPtr& fp, const TileBase&
   return hipGetLastError();
 }
 
-hipError_t launch_seg_reduce(const SegArgs& a, const FieldPtr& fp, int64_t nnz_total, Profiler* prof,
-                             hipStream_t s) {
+__global__ void zero_counters_kernel(int32_t* c) {
+  if (threadIdx.x < 2) c[threadIdx.x] = 0;
+}
+
+hipError_t launch_zero_counters(int32_t* counters, hipStream_t s) {
+  hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, counters);
+  return hipGetLastError();
+}
+
+hipError_t launch_seg_reduce(const SegArgs& a, int64_t nnz_total, Profiler* prof, hipStream_t s) {
   if (nnz_total == 0) return hipSuccess;
   const int groups_per_block = 256 / (a.D >> 2);
-  int64_t blocks = (nnz_total + groups_per_block - 1) / groups_per_block;
-  if (blocks > 256 * 32) blocks = 256 * 32;
-  {
-    ProfScope ps(prof, KID_SEG_REDUCE, s);
-    hipLaunchKernelGGL(seg_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a, fp);
-  }
-  {
-    ProfScope ps(prof, KID_SEG_REDUCE_LONG, s);
-    hipLaunchKernelGGL(seg_reduce_long_kernel, dim3(1024), dim3(256), 0, s, a, fp);
+  int64_t nb = (nnz_total + groups_per_block - 1) / groups_per_block;
+  if (nb > 256 * 32) nb = 256 * 32;
+  const unsigned blocks = (unsigned)nb;
+  if (a.update) {
+    if (a.table_bf16) {
+      if (a.rowwise) launch_reduce_variant<bf16_t, true, true>(a, blocks, prof, s);
+      else launch_reduce_variant<bf16_t, false, true>(a, blocks, prof, s);
+    } else {
+      if (a.rowwise) launch_reduce_variant<float, true, true>(a, blocks, prof, s);
+      else launch_reduce_variant<float, false, true>(a, blocks, prof, s);
+    }
+  } else {
+    launch_reduce_variant<float, false, false>(a, blocks, prof, s);
   }
   return hipGetLastError();
 }

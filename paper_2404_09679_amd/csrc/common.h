@@ -203,6 +203,7 @@ struct SortBuffers {
   int32_t* key[2];
   int32_t* pay[2];
   uint32_t* hist;                  // [total_tiles << radix_bits]
+  uint32_t* digit_base;            // [F << radix_bits]
 };
 hipError_t launch_sort_pass(const SortPlan& pl, const SortBuffers& sb, int pass, const FieldPtr& fp,
                             const TileBase& tb, Profiler* prof, hipStream_t s);
@@ -212,20 +213,30 @@ struct SegArgs {
   const int32_t* pay;              // sample index of each sorted lookup
   int32_t* tile_heads;             // [total_tiles + 1] heads per tile -> exclusive prefix
   int32_t* ubase;                  // [F + 1] first unique of each field; ubase[F] = U
-  int32_t* uniq;                   // [U]
-  int32_t* segoff;                 // [U + F], field f's slice starts at ubase[f] + f
+  int32_t* uniq;                   // [U] row id of each run
+  int32_t* ufield;                 // [U] field of each run
+  int32_t* segabs;                 // [U + 1] start of each run in the sorted arrays (all fields)
+  int32_t* segoff;                 // [U + F], per-field offsets; field f's slice starts at ubase[f] + f
   float* sample_w;                 // [B]
-  int32_t* long_count;             // [1]
-  int32_t* long_list;              // [cap]
-  float* G;                        // [U, D]
+  int32_t* counters;               // [2]: number of long runs, number of chunk work items
+  int32_t* long_seg;               // [long_cap][3]: run, first item, number of chunks
+  int32_t* items;                  // [item_cap][2]: run, chunk index
+  float* partial;                  // [item_cap, D] chunk sums of long runs
+  float* G;                        // [U, D] coalesced gradient (written when not updating)
   const float* dx;                 // [B, lddx]
   int64_t lddx;
-  int32_t F, D, B, max_tiles, total_tiles, long_threshold, long_cap;
+  int32_t F, D, B, max_tiles, total_tiles, long_threshold, chunk, long_cap, item_cap;
+  // parameter update fused into the reduction (update != 0)
+  int32_t update, table_bf16, rowwise;
+  void* tables;
+  float* state;
+  int64_t R;
+  float lr, eps;
 };
 hipError_t launch_segments(const SegArgs& a, const FieldPtr& fp, const TileBase& tb,
                            const ShardTab& tab, Profiler* prof, hipStream_t s);
-hipError_t launch_seg_reduce(const SegArgs& a, const FieldPtr& fp, int64_t nnz_total, Profiler* prof,
-                             hipStream_t s);
+hipError_t launch_seg_reduce(const SegArgs& a, int64_t nnz_total, Profiler* prof, hipStream_t s);
+hipError_t launch_zero_counters(int32_t* counters, hipStream_t s);
 
 // ---------------------------------------------------------------- optim.hip
 struct DenseAggArgs {
@@ -234,19 +245,6 @@ struct DenseAggArgs {
   int64_t P;
 };
 hipError_t launch_dense_agg(const DenseAggArgs& a, const ShardTab& tab, hipStream_t s);
-
-struct SparseAdagradArgs {
-  void* tables;
-  float* state;
-  const float* G;
-  const int32_t* uniq;
-  const int32_t* ubase;  // [F+1]
-  int64_t R;
-  int32_t F, D, table_bf16, rowwise;
-  float lr, eps;
-  int64_t max_rows;      // upper bound on U (sizes the grid)
-};
-hipError_t launch_sparse_adagrad(const SparseAdagradArgs& a, hipStream_t s);
 
 struct DenseAdagradArgs {
   float* p;

@@ -87,7 +87,9 @@ struct antdt_ctx {
   int sort_passes = 1, radix_bits = 1;
   int64_t max_tiles_total = 0;
   int long_threshold = 64;
-  int64_t long_cap = 0;
+  int64_t long_cap = 0, item_cap = 0;
+  int chunk = 256;
+  bool g_valid = false;
   size_t ws_bytes = 0;
   // caller's buffers
   void* tables = nullptr;
@@ -107,8 +109,9 @@ struct antdt_ctx {
   int64_t ldt = 0;
   int32_t* lookup_sample = nullptr;
   int32_t *key[2] = {}, *pay[2] = {}, *tile_heads = nullptr, *ubase = nullptr, *uniq = nullptr;
-  int32_t *segoff = nullptr, *long_count = nullptr, *long_list = nullptr;
-  uint32_t* hist = nullptr;
+  int32_t *segoff = nullptr, *ufield = nullptr, *segabs = nullptr, *counters = nullptr, *long_seg = nullptr, *items = nullptr;
+  float* partial = nullptr;
+  uint32_t *hist = nullptr, *digit_base = nullptr;
   // batch
   const int32_t* ids = nullptr;
   const int32_t* offsets = nullptr;
@@ -125,6 +128,10 @@ struct antdt_ctx {
   bool stepped[ANTDT_MAX_SHARDS] = {};
   bool included[ANTDT_MAX_SHARDS] = {};
   int sorted_buf = 0;
+  // side stream on which the coalescing structure of a batch is built while the MLP runs
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  bool presorted = false;
 };
 
 static int fail(antdt_ctx* c, int code, const std::string& msg) {
@@ -185,12 +192,17 @@ static size_t carve(antdt_ctx* c, char* base) {
     c->pay[i] = (int32_t*)take((size_t)N * 4);
   }
   c->hist = (uint32_t*)take((size_t)(c->max_tiles_total << c->radix_bits) * 4);
+  c->digit_base = (uint32_t*)take((size_t)(m.num_fields << c->radix_bits) * 4);
   c->tile_heads = (int32_t*)take((size_t)(c->max_tiles_total + 1) * 4);
   c->ubase = (int32_t*)take((size_t)(m.num_fields + 1) * 4);
   c->uniq = (int32_t*)take((size_t)N * 4);
   c->segoff = (int32_t*)take((size_t)(N + m.num_fields + 1) * 4);
-  c->long_count = (int32_t*)take(4);
-  c->long_list = (int32_t*)take((size_t)c->long_cap * 4);
+  c->ufield = (int32_t*)take((size_t)N * 4);
+  c->segabs = (int32_t*)take((size_t)(N + 1) * 4);
+  c->counters = (int32_t*)take(8);
+  c->long_seg = (int32_t*)take((size_t)c->long_cap * 12);
+  c->items = (int32_t*)take((size_t)c->item_cap * 8);
+  c->partial = (float*)take((size_t)c->item_cap * m.dim * 4);
   c->G = (float*)take((size_t)N * m.dim * 4);
   return off;
 }
@@ -249,6 +261,7 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
   c->radix_bits = (bits + c->sort_passes - 1) / c->sort_passes;
   c->max_tiles_total = m.max_nnz / 4096 + m.num_fields + 1;
   c->long_cap = m.max_nnz / c->long_threshold + 1;
+  c->item_cap = m.max_nnz / c->chunk + c->long_cap + 1;
   c->ws_bytes = carve(c, nullptr);
   memset(&c->tab, 0, sizeof(c->tab));
   *out = c;
@@ -258,6 +271,12 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
 int antdt_destroy(antdt_ctx* ctx) {
   if (!ctx) return ANTDT_OK;
   prof_drain(&ctx->prof);
+  if (ctx->side) {
+    (void)hipStreamSynchronize(ctx->side);
+    (void)hipStreamDestroy(ctx->side);
+    (void)hipEventDestroy(ctx->ev_fork);
+    (void)hipEventDestroy(ctx->ev_join);
+  }
   for (auto& e : ctx->prof.pool) {
     (void)hipEventDestroy(e.first);
     (void)hipEventDestroy(e.second);
@@ -326,13 +345,17 @@ int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params
   c->params = mlp_params;
   c->pstate = mlp_state;
   carve(c, (char*)workspace);
+  if (!c->side) {
+    HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
+  }
   c->stage = ST_BOUND;
   return refresh_bf16_weights(c, (hipStream_t)stream);
 }
 
 int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, const int32_t* offsets,
                     const float* dense, const float* labels, int64_t B, void* stream) {
-  (void)stream;
   if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_batch: null context");
   if (c->stage < ST_BOUND) return fail(c, ANTDT_BAD_STATE, "antdt_set_batch: call antdt_bind first");
   if (!field_ptr || !offsets || !labels || (c->m.num_dense > 0 && !dense))
@@ -364,6 +387,8 @@ int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, 
   c->labels = labels;
   c->B = B;
   c->stage = ST_BATCH;
+  if (c->presorted) HIP_TRY(c, hipStreamWaitEvent((hipStream_t)stream, c->ev_join, 0));
+  c->presorted = false;
   memset(c->stepped, 0, sizeof(c->stepped));
   return ANTDT_OK;
 }
@@ -425,9 +450,62 @@ int antdt_assign_shard(antdt_ctx* c, int64_t B, int32_t K, const int64_t* sizes,
   }
   for (int k = K; k < ANTDT_MAX_SHARDS; ++k) c->tab.start[k] = (int32_t)s;
   c->have_shards = true;
+  c->presorted = false;
   c->shard_B = B;
   memset(c->stepped, 0, sizeof(c->stepped));
   if (c->stage == ST_AGGREGATED) c->stage = ST_BATCH;
+  return ANTDT_OK;
+}
+
+static void fill_seg_args(antdt_ctx* c, SegArgs& a) {
+  const antdt_model& m = c->m;
+  memset(&a, 0, sizeof(a));
+  a.key = c->key[c->sorted_buf]; a.pay = c->pay[c->sorted_buf];
+  a.tile_heads = c->tile_heads; a.ubase = c->ubase; a.uniq = c->uniq; a.ufield = c->ufield;
+  a.segabs = c->segabs; a.segoff = c->segoff; a.sample_w = c->sample_w; a.counters = c->counters;
+  a.long_seg = c->long_seg; a.items = c->items; a.partial = c->partial;
+  a.G = c->G; a.dx = c->dx; a.lddx = c->FD;
+  a.F = m.num_fields; a.D = m.dim; a.B = (int32_t)c->B; a.max_tiles = c->max_tiles;
+  a.total_tiles = c->total_tiles; a.long_threshold = c->long_threshold; a.chunk = c->chunk;
+  a.long_cap = (int32_t)c->long_cap; a.item_cap = (int32_t)c->item_cap;
+  a.tables = c->tables; a.state = c->table_state; a.R = m.rows_per_field; a.lr = m.lr; a.eps = m.eps;
+  a.table_bf16 = m.table_dtype == ANTDT_BF16; a.rowwise = m.adagrad_state == ANTDT_STATE_ROWWISE;
+}
+
+// Resets the long-run queues (the reduction kernels fill them again).
+static int reset_queues(antdt_ctx* c, hipStream_t s) {
+  HIP_TRY(c, launch_zero_counters(c->counters, s));
+  return ANTDT_OK;
+}
+
+static void set_weights(antdt_ctx* c) {
+  const int K = c->tab.K;
+  int64_t tot = 0;
+  for (int k = 0; k < K; ++k)
+    if (c->included[k]) tot += c->tab.len[k];
+  for (int k = 0; k < ANTDT_MAX_SHARDS; ++k)
+    c->tab.w[k] = (k < K && c->included[k] && tot > 0) ? (float)((double)c->tab.len[k] / (double)tot) : 0.0f;
+}
+
+// Sort the lookups by row id, find the runs, and fill the per-sample weights: everything of
+// the server side that depends only on the batch's ids and on the shard weights.
+static int build_coalescing(antdt_ctx* c, hipStream_t s) {
+  Profiler* pr = prof_of(c);
+  const antdt_model& m = c->m;
+  SortPlan pl;
+  pl.F = m.num_fields; pl.B = (int32_t)c->B; pl.passes = c->sort_passes; pl.radix_bits = c->radix_bits;
+  pl.max_tiles = c->max_tiles; pl.total_tiles = c->total_tiles;
+  SortBuffers sb;
+  sb.ids = c->ids; sb.offsets = c->offsets;
+  sb.key[0] = c->key[0]; sb.key[1] = c->key[1]; sb.pay[0] = c->pay[0]; sb.pay[1] = c->pay[1];
+  sb.hist = c->hist;
+  sb.digit_base = c->digit_base;
+  sb.pay0 = c->lookup_sample;
+  for (int p = 0; p < pl.passes; ++p) HIP_TRY(c, launch_sort_pass(pl, sb, p, c->fp, c->tb, pr, s));
+  c->sorted_buf = (pl.passes - 1) & 1;
+  SegArgs a;
+  fill_seg_args(c, a);
+  HIP_TRY(c, launch_segments(a, c->fp, c->tb, c->tab, pr, s));
   return ANTDT_OK;
 }
 
@@ -436,6 +514,10 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
   if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_worker_step: call antdt_set_batch first");
   if (!c->have_shards || c->shard_B != c->B)
     return fail(c, ANTDT_BAD_STATE, "antdt_worker_step: antdt_assign_shard with the batch's B is required");
+  if (c->presorted) {  // an earlier batched step whose aggregate never came: let its side work finish
+    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
+    c->presorted = false;
+  }
   Profiler* pr = prof_of(c);
   const antdt_model& m = c->m;
   const ShardTab& tab = c->tab;
@@ -452,6 +534,19 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     a.xt = c->act_bf16 ? c->act_t[0] : nullptr; a.ldt = c->ldt; a.lookup_sample = c->lookup_sample;
     ProfScope ps(pr, KID_POOL, s);
     HIP_TRY(c, launch_pool(a, c->fp, s));
+  }
+  c->presorted = false;
+  if (k0 == 0 && k1 == tab.K && c->side) {
+    // All shards in one pass: the ids and the sample index of every lookup are known now, so
+    // the sort and the run detection of the coming aggregate can run beside the MLP.
+    for (int k = 0; k < tab.K; ++k) c->included[k] = true;
+    set_weights(c);
+    HIP_TRY(c, hipEventRecord(c->ev_fork, s));
+    HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+    const int rc = build_coalescing(c, c->side);
+    if (rc) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
+    c->presorted = true;
   }
   auto act = [&](int l) -> char* { return l == 0 ? c->x : c->h[l]; };
   auto ld = [&](int l) -> int64_t { return l == 0 ? c->ldx : c->width[l]; };
@@ -600,43 +695,28 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
     return fail(c, ANTDT_BAD_STATE, "antdt_aggregate: set_batch, assign_shard and worker_step come first");
   hipStream_t s = (hipStream_t)stream;
   Profiler* pr = prof_of(c);
-  const antdt_model& m = c->m;
   const int K = c->tab.K;
-  int64_t tot = 0;
   for (int k = 0; k < K; ++k) {
     c->included[k] = !shard_mask || shard_mask[k];
     if (c->included[k]) {
       if (c->tab.len[k] > 0 && !c->stepped[k])
         return fail(c, ANTDT_BAD_STATE, "antdt_aggregate: an included shard has no worker_step result");
-      tot += c->tab.len[k];
     } else if (c->tab.len[k] > 0) {
       return fail(c, ANTDT_UNSUPPORTED, "antdt_aggregate: leaving out a non-empty shard is not implemented");
     }
   }
-  for (int k = 0; k < ANTDT_MAX_SHARDS; ++k)
-    c->tab.w[k] = (k < K && c->included[k] && tot > 0) ? (float)((double)c->tab.len[k] / (double)tot) : 0.0f;
-
-  SortPlan pl;
-  pl.F = m.num_fields; pl.B = (int32_t)c->B; pl.passes = c->sort_passes; pl.radix_bits = c->radix_bits;
-  pl.max_tiles = c->max_tiles; pl.total_tiles = c->total_tiles;
-  SortBuffers sb;
-  sb.ids = c->ids; sb.offsets = c->offsets;
-  sb.key[0] = c->key[0]; sb.key[1] = c->key[1]; sb.pay[0] = c->pay[0]; sb.pay[1] = c->pay[1];
-  sb.hist = c->hist;
-  sb.pay0 = c->lookup_sample;
-  for (int p = 0; p < pl.passes; ++p) HIP_TRY(c, launch_sort_pass(pl, sb, p, c->fp, c->tb, pr, s));
-  c->sorted_buf = (pl.passes - 1) & 1;
-
-  SegArgs a;
-  memset(&a, 0, sizeof(a));
-  a.key = c->key[c->sorted_buf]; a.pay = c->pay[c->sorted_buf];
-  a.tile_heads = c->tile_heads; a.ubase = c->ubase; a.uniq = c->uniq; a.segoff = c->segoff;
-  a.sample_w = c->sample_w; a.long_count = c->long_count; a.long_list = c->long_list;
-  a.G = c->G; a.dx = c->dx; a.lddx = c->FD;
-  a.F = m.num_fields; a.D = m.dim; a.B = (int32_t)c->B; a.max_tiles = c->max_tiles;
-  a.total_tiles = c->total_tiles; a.long_threshold = c->long_threshold; a.long_cap = (int32_t)c->long_cap;
-  HIP_TRY(c, launch_segments(a, c->fp, c->tb, c->tab, pr, s));
-  HIP_TRY(c, launch_seg_reduce(a, c->fp, c->fp.p[m.num_fields], pr, s));
+  bool all = true;
+  for (int k = 0; k < K; ++k) all = all && c->included[k];
+  if (c->presorted && all) {
+    // the batched worker step already built the structure on the side stream
+    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  } else {
+    set_weights(c);
+    const int rc = build_coalescing(c, s);
+    if (rc) return rc;
+  }
+  c->presorted = false;
+  c->g_valid = false;
   {
     DenseAggArgs d;
     d.grads = c->shard_grads; d.g = c->g_dense; d.P = c->P;
@@ -653,14 +733,15 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   Profiler* pr = prof_of(c);
   const antdt_model& m = c->m;
-  {
-    SparseAdagradArgs a;
-    a.tables = c->tables; a.state = c->table_state; a.G = c->G; a.uniq = c->uniq; a.ubase = c->ubase;
-    a.R = m.rows_per_field; a.F = m.num_fields; a.D = m.dim;
-    a.table_bf16 = m.table_dtype == ANTDT_BF16; a.rowwise = m.adagrad_state == ANTDT_STATE_ROWWISE;
-    a.lr = m.lr; a.eps = m.eps; a.max_rows = c->fp.p[m.num_fields];
-    ProfScope ps(pr, KID_SPARSE_ADAGRAD, s);
-    HIP_TRY(c, launch_sparse_adagrad(a, s));
+  {  // weighted run sums with the Adagrad step of every touched row applied on the spot
+    SegArgs a;
+    fill_seg_args(c, a);
+    a.update = 1;
+    if (c->g_valid) {  // a view ran the reduction already and filled the queues
+      const int rc = reset_queues(c, s);
+      if (rc) return rc;
+    }
+    HIP_TRY(c, launch_seg_reduce(a, c->fp.p[m.num_fields], pr, s));
   }
   {
     DenseAdagradArgs a;
@@ -753,6 +834,14 @@ int antdt_view_coalesced(antdt_ctx* c, int32_t f, const int32_t** unique_ids, co
     return fail(c, ANTDT_INVALID_ARG, "antdt_view_coalesced: null argument");
   if (f < 0 || f >= c->m.num_fields) return fail(c, ANTDT_INVALID_ARG, "antdt_view_coalesced: field out of range");
   if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_coalesced: call antdt_aggregate first");
+  if (c->stage != ST_AGGREGATED) return fail(c, ANTDT_BAD_STATE, "antdt_view_coalesced: valid between antdt_aggregate and antdt_apply_update");
+  if (!c->g_valid) {  // the coalesced sums are only written out on request
+    SegArgs a;
+    fill_seg_args(c, a);
+    a.update = 0;
+    HIP_TRY(c, launch_seg_reduce(a, c->fp.p[c->m.num_fields], prof_of(c), (hipStream_t)stream));
+    c->g_valid = true;
+  }
   int32_t ub[2];
   HIP_TRY(c, hipMemcpyAsync(ub, c->ubase + f, sizeof(ub), hipMemcpyDeviceToHost, (hipStream_t)stream));
   HIP_TRY(c, hipStreamSynchronize((hipStream_t)stream));

@@ -21,72 +21,6 @@ __global__ __launch_bounds__(256) void dense_agg_kernel(DenseAggArgs a, ShardTab
   }
 }
 
-__device__ __forceinline__ int field_of_unique(const int32_t* ubase, int F, int64_t u) {
-  int lo = 0, hi = F;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (ubase[mid] <= u) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
-// Row-sparse Adagrad: a group of D/4 lanes owns one touched row.
-//   element-wise: S += g^2;               p -= lr * g / (sqrt(S) + eps)
-//   row-wise:     S[r] += mean_d g[r,d]^2; p -= lr * g / (sqrt(S[r]) + eps)
-template <typename TT, bool ROWWISE>
-__global__ __launch_bounds__(256) void sparse_adagrad_kernel(SparseAdagradArgs a) {
-  const int lps = a.D >> 2;
-  const int groups_per_block = 256 / lps;
-  const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
-  const int64_t U = a.ubase[a.F];
-  TT* tables = reinterpret_cast<TT*>(a.tables);
-  for (int64_t u = (int64_t)blockIdx.x * groups_per_block + g; u < U; u += (int64_t)gridDim.x * groups_per_block) {
-    const int f = field_of_unique(a.ubase, a.F, u);
-    const int64_t row = (int64_t)f * a.R + min(max((int64_t)a.uniq[u], (int64_t)0), a.R - 1);
-    const float4 gr = *reinterpret_cast<const float4*>(a.G + u * a.D + c * 4);
-    TT* prow = tables + row * a.D + c * 4;
-    float p[4];
-    if (sizeof(TT) == 4) {
-      const float4 v = *reinterpret_cast<const float4*>(prow);
-      p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w;
-    } else {
-      const uint2 v = *reinterpret_cast<const uint2*>(prow);
-      p[0] = __uint_as_float(v.x << 16); p[1] = __uint_as_float(v.x & 0xFFFF0000u);
-      p[2] = __uint_as_float(v.y << 16); p[3] = __uint_as_float(v.y & 0xFFFF0000u);
-    }
-    const float gv[4] = {gr.x, gr.y, gr.z, gr.w};
-    float den[4];
-    if (ROWWISE) {
-      float sq = (gv[0] * gv[0] + gv[1] * gv[1]) + (gv[2] * gv[2] + gv[3] * gv[3]);
-      for (int o = 1; o < lps; o <<= 1) sq += __shfl_xor(sq, o, 64);
-      const float s1 = a.state[row] + sq / (float)a.D;
-      if (c == 0) a.state[row] = s1;
-      const float d = sqrtf(s1) + a.eps;
-      den[0] = den[1] = den[2] = den[3] = d;
-    } else {
-      float4* srow = reinterpret_cast<float4*>(a.state + row * a.D + c * 4);
-      float4 sv = *srow;
-      sv.x = fmaf(gv[0], gv[0], sv.x);
-      sv.y = fmaf(gv[1], gv[1], sv.y);
-      sv.z = fmaf(gv[2], gv[2], sv.z);
-      sv.w = fmaf(gv[3], gv[3], sv.w);
-      *srow = sv;
-      den[0] = sqrtf(sv.x) + a.eps; den[1] = sqrtf(sv.y) + a.eps;
-      den[2] = sqrtf(sv.z) + a.eps; den[3] = sqrtf(sv.w) + a.eps;
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) p[e] -= a.lr * gv[e] / den[e];
-    if (sizeof(TT) == 4) {
-      *reinterpret_cast<float4*>(prow) = make_float4(p[0], p[1], p[2], p[3]);
-    } else {
-      uint2 o;
-      o.x = (uint32_t)f2bf(p[0]) | ((uint32_t)f2bf(p[1]) << 16);
-      o.y = (uint32_t)f2bf(p[2]) | ((uint32_t)f2bf(p[3]) << 16);
-      *reinterpret_cast<uint2*>(prow) = o;
-    }
-  }
-}
-
 // Dense Adagrad on the MLP parameters, refreshing the bf16 operand copies in the same pass.
 __global__ __launch_bounds__(256) void dense_adagrad_kernel(DenseAdagradArgs a) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -154,22 +88,6 @@ hipError_t launch_dense_agg(const DenseAggArgs& a, const ShardTab& tab, hipStrea
   int64_t blocks = (a.P + 255) / 256;
   if (blocks > 8192) blocks = 8192;
   hipLaunchKernelGGL(dense_agg_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a, tab);
-  return hipGetLastError();
-}
-
-hipError_t launch_sparse_adagrad(const SparseAdagradArgs& a, hipStream_t s) {
-  if (a.max_rows <= 0) return hipSuccess;
-  const int groups_per_block = 256 / (a.D >> 2);
-  int64_t blocks = (a.max_rows + groups_per_block - 1) / groups_per_block;
-  if (blocks > 256 * 32) blocks = 256 * 32;
-  dim3 grid((unsigned)blocks), block(256);
-  if (a.table_bf16) {
-    if (a.rowwise) hipLaunchKernelGGL((sparse_adagrad_kernel<bf16_t, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((sparse_adagrad_kernel<bf16_t, false>), grid, block, 0, s, a);
-  } else {
-    if (a.rowwise) hipLaunchKernelGGL((sparse_adagrad_kernel<float, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((sparse_adagrad_kernel<float, false>), grid, block, 0, s, a);
-  }
   return hipGetLastError();
 }
 
