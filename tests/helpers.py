@@ -62,9 +62,19 @@ def rel_err(a, b):
     return float(np.linalg.norm(a - b)) / nb, float(np.max(np.abs(a - b))) / mb
 
 
-def assert_close(a, b, tol, what=""):
+def assert_close(a, b, tol, what="", max_tol=None):
+    """Both error measures under `tol`; `max_tol` loosens the element-wise one (see BF16_MAX_TOL)."""
     n, m = rel_err(a, b)
-    assert n <= tol and m <= tol, f"{what}: normwise {n:.3e}, maxwise {m:.3e} > {tol:.1e}"
+    mt = tol if max_tol is None else max_tol
+    assert n <= tol and m <= mt, f"{what}: normwise {n:.3e} (<= {tol:.1e}), maxwise {m:.3e} (<= {mt:.1e})"
+
+
+# Gradients downstream of bf16-rounded activations: where an activation sits within rounding of
+# zero, fp32 and float64 accumulation can round it to different sides, the ReLU decision of
+# that one unit flips, and the gradient row of that one sample changes by O(1) relative to
+# itself.  Such isolated elements are bounded by BF16_MAX_TOL of the tensor's largest entry;
+# the normwise error stays under the 2e-2 bound.
+BF16_MAX_TOL = 0.25
 
 
 TINY = wl.RankingConfig("tiny", 2, 7, 3, "f32", "elementwise", 2, (8, 4, 1), "f32", 3, 1.05,
