@@ -212,8 +212,10 @@ int antdt_view_pooled(antdt_ctx* ctx, int32_t k, const void** x, int64_t* rows, 
 /* Shard k's dense gradient (fp32, flat layout) and d loss_k / d pooled (fp32 [B_k, ld_dx]). */
 int antdt_view_shard_grads(antdt_ctx* ctx, int32_t k, const float** dense, const float** dx,
                            int64_t* ld_dx);
-/* Aggregated dense gradient (fp32, flat layout). */
-int antdt_view_dense_grad(antdt_ctx* ctx, const float** g);
+/* Aggregated dense gradient (fp32, flat layout), written out on this request (apply_update
+ * forms the same sum inside its optimizer kernel).  Enqueues on `stream`; valid between
+ * antdt_aggregate and antdt_apply_update. */
+int antdt_view_dense_grad(antdt_ctx* ctx, const float** g, void* stream);
 /* Coalesced sparse gradient of field f after antdt_aggregate: unique_ids int32 [U_f] ascending,
  * seg_offsets int32 [U_f + 1], seg_samples int32 [nnz_f] (global sample index of every sorted
  * lookup; inside a run ascending), G fp32 [U_f, D].  Synchronises `stream`. */

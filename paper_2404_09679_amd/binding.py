@@ -64,7 +64,7 @@ def _load():
     lib.antdt_fill_tables.argtypes = [vp, i32, i32, i64, i32, f32, vp]
     lib.antdt_view_pooled.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)]
     lib.antdt_view_shard_grads.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64)]
-    lib.antdt_view_dense_grad.argtypes = [vp, C.POINTER(vp)]
+    lib.antdt_view_dense_grad.argtypes = [vp, C.POINTER(vp), vp]
     lib.antdt_view_coalesced.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                          C.POINTER(i64), C.POINTER(i64), C.POINTER(vp), vp]
     lib.antdt_profile.argtypes = [vp, i32, i32]
@@ -218,7 +218,7 @@ class Context:
 
     def view_dense_grad(self) -> torch.Tensor:
         g = C.c_void_p()
-        self._check(lib.antdt_view_dense_grad(self._h, C.byref(g)))
+        self._check(lib.antdt_view_dense_grad(self._h, C.byref(g), _stream()))
         P = sum(self.model.layer_sizes[i] * self.model.layer_sizes[i + 1] + self.model.layer_sizes[i + 1]
                 for i in range(self.model.num_layers))
         return self._ws_view(g.value, P * 4, torch.float32)

@@ -240,25 +240,34 @@ hipError_t launch_zero_counters(int32_t* counters, hipStream_t s);
 
 // ---------------------------------------------------------------- optim.hip
 struct DenseAggArgs {
-  const float* grads;  // [K, P]
+  const float* grads;  // [K, stride] per-shard flat gradients
   float* g;            // [P]
-  int64_t P;
+  int64_t P, stride;
 };
 hipError_t launch_dense_agg(const DenseAggArgs& a, const ShardTab& tab, hipStream_t s);
 
+// Dense Adagrad on the flat MLP parameters with the gradient aggregated on the fly
+// (g = sum_k w_k grads[k]).  Hidden-layer weight matrices are walked in 64x64 tiles so that
+// both bf16 operand copies (W as [in,out] and W^T as [out,in_pad]) are refreshed with
+// coalesced stores in the same pass; everything else (biases, the last layer) goes through
+// plain ranges.
 struct DenseAdagradArgs {
   float* p;
   float* state;
-  const float* g;
-  int64_t P;
+  const float* grads;  // [K, stride]
+  int64_t stride;
   float lr, eps;
-  // bf16 operand copies of the hidden-layer weights: copy[l] mirrors p[w_off[l] .. +w_len[l])
-  int32_t n_copy;
+  int32_t n_mat;
   int64_t w_off[ANTDT_MAX_LAYERS];
-  int64_t w_len[ANTDT_MAX_LAYERS];
-  bf16_t* copy[ANTDT_MAX_LAYERS];
+  int32_t rows[ANTDT_MAX_LAYERS], cols[ANTDT_MAX_LAYERS], rows_pad[ANTDT_MAX_LAYERS];
+  bf16_t* wb[ANTDT_MAX_LAYERS];
+  bf16_t* wbt[ANTDT_MAX_LAYERS];
+  int32_t tile_base[ANTDT_MAX_LAYERS + 1];
+  int32_t n_rng;
+  int64_t rng_off[ANTDT_MAX_LAYERS + 1], rng_len[ANTDT_MAX_LAYERS + 1];
+  int32_t rng_block[ANTDT_MAX_LAYERS + 2];  // first block of each range, relative to the first range block
 };
-hipError_t launch_dense_adagrad(const DenseAdagradArgs& a, hipStream_t s);
+hipError_t launch_dense_adagrad(const DenseAdagradArgs& a, const ShardTab& tab, hipStream_t s);
 
 struct AdamArgs {
   float* p;

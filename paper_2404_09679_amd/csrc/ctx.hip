@@ -81,7 +81,8 @@ struct antdt_ctx {
   int L = 0, FD = 0, in0 = 0, ldx = 0;
   int act_bf16 = 0;
   size_t act_size = 4;
-  int64_t P = 0;
+  int64_t P = 0, Pstride = 0;  // Pstride: P rounded up to 4 (per-shard gradient pitch)
+  bool gdense_valid = false;
   int64_t w_off[ANTDT_MAX_LAYERS], b_off[ANTDT_MAX_LAYERS];
   int width[ANTDT_MAX_LAYERS + 1];  // width[l] = layer_sizes[l]
   int sort_passes = 1, radix_bits = 1;
@@ -172,7 +173,7 @@ static size_t carve(antdt_ctx* c, char* base) {
   c->sample_w = (float*)take(Bm * 4);
   c->loss_k = (float*)take(K * 4);
   c->dx = (float*)take((size_t)Bm * c->FD * 4);
-  c->shard_grads = (float*)take((size_t)K * c->P * 4);
+  c->shard_grads = (float*)take((size_t)K * c->Pstride * 4);
   c->g_dense = (float*)take((size_t)c->P * 4);
   if (c->act_bf16) {
     for (int l = 0; l + 1 < c->L; ++l) {
@@ -255,6 +256,7 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
     off += c->width[l + 1];
   }
   c->P = off;
+  c->Pstride = (off + 3) / 4 * 4;
   int bits = 1;
   while ((1ll << bits) < m.rows_per_field) ++bits;
   c->sort_passes = (bits + 9) / 10;
@@ -585,6 +587,11 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       a.dh = c->dx; a.lddh = c->FD; a.dh_cols = c->FD; a.relu = 0; a.bf16_dh = 0;
     }
     a.k_begin = k0; a.k_end = k1;
+    const bool head_writes_dht = c->act_bf16 && L > 1 && c->width[L - 1] <= 4096;
+    if (head_writes_dht) {
+      a.dht = c->dh_t[L - 1];
+      a.ldt = c->ldt;
+    }
     {
       ProfScope ps(pr, KID_HEAD, s);
       HIP_TRY(c, launch_head(a, tab, s));
@@ -593,7 +600,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     memset(&r, 0, sizeof(r));
     r.h = act(L - 1); r.ldh = ld(L - 1); r.width = c->width[L - 1]; r.bf16_h = c->act_bf16;
     r.dz = c->dz; r.loss_s = c->loss_s; r.grads = c->shard_grads; r.loss_k = c->loss_k; r.loss_out = loss_out;
-    r.P = c->P; r.w_off = c->w_off[L - 1]; r.b_off = c->b_off[L - 1]; r.k_begin = k0; r.k_end = k1;
+    r.P = c->Pstride; r.w_off = c->w_off[L - 1]; r.b_off = c->b_off[L - 1]; r.k_begin = k0; r.k_end = k1;
     if (c->act_bf16 && L > 1) {
       r.ht = c->act_t[L - 1];
       r.ldt = c->ldt;
@@ -602,7 +609,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       ProfScope ps(pr, KID_HEAD_REDUCE, s);
       HIP_TRY(c, launch_head_reduce(r, tab, s));
     }
-    if (c->act_bf16 && L > 1) {  // the weight-gradient product wants dh^T
+    if (c->act_bf16 && L > 1 && !head_writes_dht) {  // the weight-gradient product wants dh^T
       TransposeArgs t;
       memset(&t, 0, sizeof(t));
       t.n = 1;
@@ -627,7 +634,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
       g.M = c->width[l] + 1; g.N = c->width[l + 1]; g.K = 0;
       g.epi = EPI_PLAIN; g.bf16_in = 1; g.bf16_out = 0;
-      g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->P;
+      g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
       ProfScope ps(pr, KID_GEMM_WGRAD, s);
       HIP_TRY(c, launch_gemm(g, tab, s));
     } else {
@@ -639,14 +646,14 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
         g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
         g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
         g.epi = EPI_PLAIN; g.bf16_in = 0; g.bf16_out = 0;
-        g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->P;
+        g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
         ProfScope ps(pr, KID_GEMM_WGRAD, s);
         HIP_TRY(c, launch_gemm(g, tab, s));
       }
       BiasGradArgs b;
       memset(&b, 0, sizeof(b));
       b.dh = c->dh[l + 1]; b.lddh = c->width[l + 1]; b.width = c->width[l + 1]; b.bf16_dh = 0;
-      b.grads = c->shard_grads; b.P = c->P; b.b_off = c->b_off[l]; b.k_begin = k0; b.k_end = k1;
+      b.grads = c->shard_grads; b.P = c->Pstride; b.b_off = c->b_off[l]; b.k_begin = k0; b.k_end = k1;
       ProfScope ps(pr, KID_BIAS_GRAD, s);
       HIP_TRY(c, launch_bias_grad(b, tab, s));
     }
@@ -694,7 +701,6 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
   if (c->stage < ST_BATCH || !c->have_shards || c->shard_B != c->B)
     return fail(c, ANTDT_BAD_STATE, "antdt_aggregate: set_batch, assign_shard and worker_step come first");
   hipStream_t s = (hipStream_t)stream;
-  Profiler* pr = prof_of(c);
   const int K = c->tab.K;
   for (int k = 0; k < K; ++k) {
     c->included[k] = !shard_mask || shard_mask[k];
@@ -717,12 +723,7 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
   }
   c->presorted = false;
   c->g_valid = false;
-  {
-    DenseAggArgs d;
-    d.grads = c->shard_grads; d.g = c->g_dense; d.P = c->P;
-    ProfScope ps(pr, KID_DENSE_AGG, s);
-    HIP_TRY(c, launch_dense_agg(d, c->tab, s));
-  }
+  c->gdense_valid = false;  // the dense sum is formed inside the optimizer kernel (or on request)
   c->stage = ST_AGGREGATED;
   return ANTDT_OK;
 }
@@ -746,20 +747,30 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
   {
     DenseAdagradArgs a;
     memset(&a, 0, sizeof(a));
-    a.p = c->params; a.state = c->pstate; a.g = c->g_dense; a.P = c->P; a.lr = m.lr; a.eps = m.eps;
-    if (c->act_bf16)
+    a.p = c->params; a.state = c->pstate; a.grads = c->shard_grads; a.stride = c->Pstride; a.lr = m.lr; a.eps = m.eps;
+    int nr = 0, rblocks = 0;
+    auto add_range = [&](int64_t off, int64_t len) {
+      a.rng_off[nr] = off; a.rng_len[nr] = len; a.rng_block[nr] = rblocks;
+      rblocks += (int)((len + 255) / 256);
+      ++nr;
+    };
+    if (c->act_bf16) {
       for (int l = 0; l + 1 < c->L; ++l) {
-        a.w_off[a.n_copy] = c->w_off[l];
-        a.w_len[a.n_copy] = (int64_t)c->width[l] * c->width[l + 1];
-        a.copy[a.n_copy] = c->wb[l];
-        ++a.n_copy;
+        a.w_off[l] = c->w_off[l]; a.rows[l] = c->width[l]; a.cols[l] = c->width[l + 1];
+        a.rows_pad[l] = l == 0 ? c->ldx : c->width[l];
+        a.wb[l] = c->wb[l]; a.wbt[l] = c->wbt[l];
+        a.tile_base[l + 1] = a.tile_base[l] + ((c->width[l] + 63) / 64) * ((c->width[l + 1] + 63) / 64);
+        add_range(c->b_off[l], c->width[l + 1]);
       }
+      a.n_mat = c->L - 1;
+      add_range(c->w_off[c->L - 1], c->P - c->w_off[c->L - 1]);
+    } else {
+      add_range(0, c->P);
+    }
+    a.n_rng = nr;
+    a.rng_block[nr] = rblocks;
     ProfScope ps(pr, KID_DENSE_ADAGRAD, s);
-    HIP_TRY(c, launch_dense_adagrad(a, s));
-  }
-  {
-    const int rc = transpose_weights(c, s);
-    if (rc) return rc;
+    HIP_TRY(c, launch_dense_adagrad(a, c->tab, s));
   }
   c->stage = ST_BATCH;
   memset(c->stepped, 0, sizeof(c->stepped));
@@ -814,15 +825,22 @@ int antdt_view_shard_grads(antdt_ctx* c, int32_t k, const float** dense, const f
   if (!c || !dense || !dx || !ld_dx) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: null argument");
   if (!c->have_shards || k < 0 || k >= c->tab.K) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: shard index out of range");
   if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_shard_grads: nothing computed yet");
-  *dense = c->shard_grads + (int64_t)k * c->P;
+  *dense = c->shard_grads + (int64_t)k * c->Pstride;
   *dx = c->dx + (int64_t)c->tab.start[k] * c->FD;
   *ld_dx = c->FD;
   return ANTDT_OK;
 }
 
-int antdt_view_dense_grad(antdt_ctx* c, const float** g) {
+int antdt_view_dense_grad(antdt_ctx* c, const float** g, void* stream) {
   if (!c || !g) return fail(c, ANTDT_INVALID_ARG, "antdt_view_dense_grad: null argument");
-  if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_dense_grad: nothing computed yet");
+  if (c->stage != ST_AGGREGATED) return fail(c, ANTDT_BAD_STATE, "antdt_view_dense_grad: valid between antdt_aggregate and antdt_apply_update");
+  if (!c->gdense_valid) {  // written out on request only; apply_update forms the same sum on the fly
+    DenseAggArgs d;
+    d.grads = c->shard_grads; d.g = c->g_dense; d.P = c->P; d.stride = c->Pstride;
+    ProfScope ps(prof_of(c), KID_DENSE_AGG, (hipStream_t)stream);
+    HIP_TRY(c, launch_dense_agg(d, c->tab, (hipStream_t)stream));
+    c->gdense_valid = true;
+  }
   *g = c->g_dense;
   return ANTDT_OK;
 }

@@ -47,6 +47,76 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a, ShardTab tab) {
   }
 }
 
+// bf16 variant working on a tile of `spb` samples staged in LDS, so that the gradient can be
+// written both row-major (dh) and transposed (dht, sample index contiguous) with coalesced
+// stores; same arithmetic as head_kernel.
+constexpr int HEAD_LDS_ELEMS = 16448;  // 32 x (512 + 2) bf16
+__global__ __launch_bounds__(256) void head_tile_kernel(HeadArgs a, ShardTab tab, int spb) {
+  __shared__ __attribute__((aligned(16))) bf16_t tile[HEAD_LDS_ELEMS];
+  __shared__ float dzs[32];
+  __shared__ float wl[4096];  // last-layer weights (global loads inside the store loops would serialise)
+  const int width = a.width, pitch = width + 2, vpr = width >> 3;
+  for (int j = threadIdx.x; j < width; j += 256) wl[j] = a.w[j];
+  const int64_t first = tab.start[a.k_begin];
+  const int64_t last = (int64_t)tab.start[a.k_end - 1] + tab.len[a.k_end - 1];
+  const int64_t s0 = first + (int64_t)blockIdx.x * spb;
+  const int rows = (int)min((int64_t)spb, last - s0);
+  const bf16_t* h = reinterpret_cast<const bf16_t*>(a.h);
+  for (int idx = threadIdx.x; idx < rows * vpr; idx += 256) {
+    const int r = idx / vpr, c8 = idx - r * vpr;
+    const uint4 v = *reinterpret_cast<const uint4*>(h + (s0 + r) * a.ldh + c8 * 8);
+    uint32_t* d = reinterpret_cast<uint32_t*>(tile + r * pitch + c8 * 8);
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int r = wave; r < rows; r += 4) {  // logits of the tile, from LDS only
+    float part = 0.0f;
+    for (int j = lane; j < width; j += 64) part = fmaf(bf2f(tile[r * pitch + j]), wl[j], part);
+    part = wave_sum(part);
+    if (lane == 0) dzs[r] = part;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < rows) {  // one thread per sample: loss and dz, their loads side by side
+    const int r = threadIdx.x;
+    const int64_t s = s0 + r;
+    const float z = dzs[r] + a.b[0];
+    int k = a.k_begin;
+    while (k + 1 < a.k_end && s >= (int64_t)tab.start[k] + tab.len[k]) ++k;
+    const float y = a.labels[s];
+    const float e = expf(-fabsf(z));
+    const float sig = z >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+    const float dz = (sig - y) * (1.0f / (float)tab.len[k]);
+    a.z[s] = z;
+    a.loss_s[s] = fmaxf(z, 0.0f) - z * y + log1pf(e);
+    a.dz[s] = dz;
+    dzs[r] = dz;
+  }
+  __syncthreads();
+  bf16_t* dh = reinterpret_cast<bf16_t*>(a.dh);
+  for (int idx = threadIdx.x; idx < rows * vpr; idx += 256) {
+    const int r = idx / vpr, c8 = idx - r * vpr;
+    const float dz = dzs[r];
+    uint32_t o[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int j = c8 * 8 + 2 * q;
+      const float g0 = bf2f(tile[r * pitch + j]) > 0.0f ? dz * wl[j] : 0.0f;
+      const float g1 = bf2f(tile[r * pitch + j + 1]) > 0.0f ? dz * wl[j + 1] : 0.0f;
+      o[q] = (uint32_t)f2bf(g0) | ((uint32_t)f2bf(g1) << 16);
+    }
+    *reinterpret_cast<uint4*>(dh + (s0 + r) * a.lddh + c8 * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+  const int ls = threadIdx.x % spb, jj = threadIdx.x / spb, jstep = 256 / spb;
+  if (ls < rows) {
+    const float dz = dzs[ls];
+    for (int j = jj; j < width; j += jstep) {
+      const float g = bf2f(tile[ls * pitch + j]) > 0.0f ? dz * wl[j] : 0.0f;
+      a.dht[(int64_t)j * a.ldt + s0 + ls] = f2bf(g);
+    }
+  }
+}
+
 // Block (64 columns x 4 sample lanes) of shard k = k_begin + blockIdx.y:
 //   dW_last[j] = sum_s h[s, j] * dz[s];  block 0 also: db_last = sum_s dz[s], loss_k = mean loss.
 template <typename TH>
@@ -156,6 +226,12 @@ hipError_t launch_head(const HeadArgs& a, const ShardTab& tab, hipStream_t s) {
   const int64_t last = (int64_t)tab.start[a.k_end - 1] + tab.len[a.k_end - 1];
   if (last <= first) return hipSuccess;
   dim3 grid((unsigned)((last - first + 3) / 4)), block(256);
+  if (a.dht) {  // bf16 hidden activation with a transposed gradient copy: tile kernel
+    int spb = 16;
+    while (spb > 4 && spb * (a.width + 2) > HEAD_LDS_ELEMS) spb >>= 1;
+    hipLaunchKernelGGL(head_tile_kernel, dim3((unsigned)((last - first + spb - 1) / spb)), block, 0, s, a, tab, spb);
+    return hipGetLastError();
+  }
   if (a.bf16_h) {
     if (a.bf16_dh) hipLaunchKernelGGL((head_kernel<bf16_t, bf16_t>), grid, block, 0, s, a, tab);
     else hipLaunchKernelGGL((head_kernel<bf16_t, float>), grid, block, 0, s, a, tab);

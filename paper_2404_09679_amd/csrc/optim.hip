@@ -8,33 +8,99 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+__device__ __forceinline__ float weighted_sum(const float* grads, int64_t stride, int64_t i, const ShardTab& tab) {
+  // Every load is issued (a branch per load would serialise them); the value of a shard
+  // with weight 0, which may never have been written, is replaced by 0 afterwards.
+  float acc = 0.0f;
+  int k = 0;
+  for (; k + 3 < tab.K; k += 4) {  // four loads in flight, added in shard order
+    float x[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) x[q] = grads[(int64_t)(k + q) * stride + i];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc = fmaf(tab.w[k + q], tab.w[k + q] != 0.0f ? x[q] : 0.0f, acc);
+  }
+  for (; k < tab.K; ++k) {
+    const float x = grads[(int64_t)k * stride + i];
+    acc = fmaf(tab.w[k], tab.w[k] != 0.0f ? x : 0.0f, acc);
+  }
+  return acc;
+}
+
 // g[i] = sum_k w_k * grads[k][i], shards added in index order.
 __global__ __launch_bounds__(256) void dense_agg_kernel(DenseAggArgs a, ShardTab tab) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.P; i += stride) {
-    float acc = 0.0f;
-    for (int k = 0; k < tab.K; ++k) {
-      const float w = tab.w[k];
-      if (w != 0.0f) acc = fmaf(w, a.grads[(int64_t)k * a.P + i], acc);
-    }
-    a.g[i] = acc;
-  }
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.P; i += stride)
+    a.g[i] = weighted_sum(a.grads, a.stride, i, tab);
 }
 
-// Dense Adagrad on the MLP parameters, refreshing the bf16 operand copies in the same pass.
-__global__ __launch_bounds__(256) void dense_adagrad_kernel(DenseAdagradArgs a) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.P; i += stride) {
-    const float g = a.g[i];
-    const float s1 = fmaf(g, g, a.state[i]);
-    const float p1 = a.p[i] - a.lr * g / (sqrtf(s1) + a.eps);
-    a.state[i] = s1;
-    a.p[i] = p1;
-    for (int l = 0; l < a.n_copy; ++l) {
-      const int64_t j = i - a.w_off[l];
-      if (j >= 0 && j < a.w_len[l]) a.copy[l][j] = f2bf(p1);
+__device__ __forceinline__ float adagrad_elem(const DenseAdagradArgs& a, const ShardTab& tab, int64_t i) {
+  const float g = weighted_sum(a.grads, a.stride, i, tab);
+  const float s1 = fmaf(g, g, a.state[i]);
+  const float p1 = a.p[i] - a.lr * g / (sqrtf(s1) + a.eps);
+  a.state[i] = s1;
+  a.p[i] = p1;
+  return p1;
+}
+
+__global__ __launch_bounds__(256) void dense_adagrad_kernel(DenseAdagradArgs a, ShardTab tab) {
+  __shared__ bf16_t tile[64][66];
+  const int nt = a.tile_base[a.n_mat];
+  if ((int)blockIdx.x < nt) {
+    int mi = 0;
+    while (mi + 1 < a.n_mat && (int)blockIdx.x >= a.tile_base[mi + 1]) ++mi;
+    const int t = blockIdx.x - a.tile_base[mi];
+    const int rows = a.rows[mi], cols = a.cols[mi];
+    const int tc = (cols + 63) / 64;
+    const int r0 = (t / tc) * 64, c0 = (t % tc) * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const bool col_ok = c0 + tx < cols;
+    // all loads of the thread's 16 elements first (indices clamped into the matrix), then the
+    // arithmetic and the stores: loads interleaved with stores would wait for one another
+    float g[16], p0[16], s0[16];
+    int64_t idx[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int r = min(r0 + ty + 4 * q, rows - 1), cc = min(c0 + tx, cols - 1);
+      idx[q] = a.w_off[mi] + (int64_t)r * cols + cc;
+      p0[q] = a.p[idx[q]];
+      s0[q] = a.state[idx[q]];
+      g[q] = 0.0f;
     }
+    for (int k = 0; k < tab.K; ++k) {  // shards in index order, 16 independent loads per shard
+      const float w = tab.w[k];
+      float x[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) x[q] = a.grads[(int64_t)k * a.stride + idx[q]];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) g[q] = fmaf(w, w != 0.0f ? x[q] : 0.0f, g[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int r = ty + 4 * q;
+      bf16_t h = 0;
+      if (r0 + r < rows && col_ok) {
+        const int64_t e = (int64_t)(r0 + r) * cols + c0 + tx;
+        const float s1 = fmaf(g[q], g[q], s0[q]);
+        const float p1 = p0[q] - a.lr * g[q] / (sqrtf(s1) + a.eps);
+        a.state[a.w_off[mi] + e] = s1;
+        a.p[a.w_off[mi] + e] = p1;
+        h = f2bf(p1);
+        a.wb[mi][e] = h;
+      }
+      tile[r][tx] = h;
+    }
+    __syncthreads();
+    for (int cidx = ty; cidx < 64; cidx += 4)
+      if (c0 + cidx < cols && r0 + tx < rows)
+        a.wbt[mi][(int64_t)(c0 + cidx) * a.rows_pad[mi] + r0 + tx] = tile[tx][cidx];
+    return;
   }
+  const int rb = blockIdx.x - nt;
+  int ri = 0;
+  while (ri + 1 < a.n_rng && rb >= a.rng_block[ri + 1]) ++ri;
+  const int64_t i = (int64_t)(rb - a.rng_block[ri]) * 256 + threadIdx.x;
+  if (i < a.rng_len[ri]) adagrad_elem(a, tab, a.rng_off[ri] + i);
 }
 
 // Weighted average of K gradient buffers fused with Adam (bias-corrected), 16 bytes per lane.
@@ -91,11 +157,10 @@ hipError_t launch_dense_agg(const DenseAggArgs& a, const ShardTab& tab, hipStrea
   return hipGetLastError();
 }
 
-hipError_t launch_dense_adagrad(const DenseAdagradArgs& a, hipStream_t s) {
-  if (a.P <= 0) return hipSuccess;
-  int64_t blocks = (a.P + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
-  hipLaunchKernelGGL(dense_adagrad_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+hipError_t launch_dense_adagrad(const DenseAdagradArgs& a, const ShardTab& tab, hipStream_t s) {
+  const int blocks = a.tile_base[a.n_mat] + a.rng_block[a.n_rng];
+  if (blocks <= 0) return hipSuccess;
+  hipLaunchKernelGGL(dense_adagrad_kernel, dim3(blocks), dim3(256), 0, s, a, tab);
   return hipGetLastError();
 }
 
