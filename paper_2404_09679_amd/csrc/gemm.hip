@@ -56,8 +56,9 @@ template <int TM, int TN, bool GROUPED>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab, int tiles_m, int tiles_n) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   constexpr int VA = BM * BK / 8 / 256, VB = BN * BK / 8 / 256;  // 16-byte vectors per thread
-  constexpr int STAGE = (BM + BN) * PITCH;  // bf16 elements of one LDS stage (A tile, then B tile)
-  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];  // two stages
+  __shared__ __attribute__((aligned(16))) bf16_t lds[(BM + BN) * PITCH];
+  bf16_t* la = lds;
+  bf16_t* lb = lds + BM * PITCH;
 
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
@@ -107,8 +108,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
     return make_uint4(val.x & all, val.y & all, val.z & all, val.w & all);
   };
   auto store_tile = [&](int kt, const uint4 (&ra)[VA], const uint4 (&rb)[VB]) {
-    bf16_t* la = lds + (kt & 1) * STAGE;
-    bf16_t* lb = la + BM * PITCH;
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
       const int v = tid + i * 256;
@@ -131,9 +130,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  auto multiply = [&](int kt) {
-    const bf16_t* la = lds + (kt & 1) * STAGE;
-    const bf16_t* lb = la + BM * PITCH;
+  auto multiply = [&]() {
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       // lane (fr, fg) supplies contraction slots fg*8 .. fg*8+7 of row fr of each 32-row tile
@@ -152,28 +149,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
     }
   };
 
-  // Two LDS stages and two register stages.  Iteration kt moves slab kt+1 from registers
-  // to the idle LDS stage, issues the loads of slab kt+3 into the freed registers and
-  // multiplies slab kt out of the other stage; one barrier per slab.  Slabs go in pairs and
-  // every load is issued unconditionally (addresses past the end are clamped, the data is
-  // zeroed by `fix`): with conditional loads the compiler cannot count the outstanding loads
-  // and drains them all before each LDS store.
+  // Slabs are processed in pairs and every load is issued unconditionally (addresses past
+  // the end are clamped, the data is zeroed by `fix`): with conditional loads the compiler
+  // cannot count outstanding loads and drains them all before each LDS store.
   const int nk = ke > kfirst ? (ke - kfirst + BK - 1) / BK : 0;
   if (nk > 0) {
     load_tile(0, ra0, rb0);
     load_tile(1, ra1, rb1);
-    store_tile(0, ra0, rb0);
-    load_tile(2, ra0, rb0);
-    __syncthreads();
   }
   for (int kt = 0; kt < nk; kt += 2) {
-    store_tile(kt + 1, ra1, rb1);
-    load_tile(kt + 3, ra1, rb1);
-    multiply(kt);
+    store_tile(kt, ra0, rb0);
     __syncthreads();
-    store_tile(kt + 2, ra0, rb0);
-    load_tile(kt + 4, ra0, rb0);
-    multiply(kt + 1);
+    load_tile(kt + 2, ra0, rb0);
+    multiply();
+    __syncthreads();
+    store_tile(kt + 1, ra1, rb1);
+    __syncthreads();
+    load_tile(kt + 3, ra1, rb1);
+    multiply();
     __syncthreads();
   }
 
@@ -372,17 +365,8 @@ template <int TM, int TN>
 void launch_bf16_variant(const GemmArgs& a, const ShardTab& tab, int groups, hipStream_t s) {
   const int tiles_m = (a.M + 64 * TM - 1) / (64 * TM), tiles_n = (a.N + 64 * TN - 1) / (64 * TN);
   dim3 grid(tiles_m * tiles_n, 1, groups);
-  constexpr size_t lds_bytes = 2 * (64 * TM + 64 * TN) * PITCH * sizeof(bf16_t);
-  static bool raised = false;  // more than the default 64 KB of LDS per block has to be asked for once
-  if (!raised) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TM, TN, true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TM, TN, false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    raised = true;
-  }
-  if (a.grouped) hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, true>), grid, dim3(256), lds_bytes, s, a, tab, tiles_m, tiles_n);
-  else hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, false>), grid, dim3(256), lds_bytes, s, a, tab, tiles_m, tiles_n);
+  if (a.grouped) hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, true>), grid, dim3(256), 0, s, a, tab, tiles_m, tiles_n);
+  else hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, false>), grid, dim3(256), 0, s, a, tab, tiles_m, tiles_n);
 }
 
 }  // namespace
