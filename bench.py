@@ -3,9 +3,9 @@
 
 A step is the whole hot path on one fresh synthetic batch that is already resident in
 HBM: set_batch + worker_step for all K shards + aggregate + apply_update (parameters are
-really updated every step; eight distinct batches are rotated).  Prints ONE JSON line.
+really updated every step; distinct resident batches are rotated).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1|cfg2|cfg3|cfg4|cfg5]
 """
 from __future__ import annotations
 
@@ -44,10 +44,13 @@ def _bytes_and_flops(cfg, stats, model):
         "sort_scatter": ("hbm", 4 * nnz + 8 * nnz + (passes - 1) * 16 * nnz),
         "seg_heads": ("hbm", 4 * nnz),
         "seg_emit": ("hbm", 4 * nnz + 8 * U),
-        "seg_reduce": ("hbm", 4 * nnz + B * F * D * 4 + U * D * 4),
-        "sparse_adagrad": ("hbm", U * (2 * D * e + 2 * state_row + 4 * D)),
-        "dense_agg": ("hbm", (K + 1) * P * 4),
-        "dense_adagrad": ("hbm", P * (5 * 4 + (2 if cfg.gemm_dtype == "bf16" else 0))),
+        # one fused kernel: segmented sum of the per-lookup gradient rows + row-sparse Adagrad
+        # (sample indices, run table, every pooled-gradient row once, touched rows and state
+        # read and written); the long-run chunk kernels work on the same bytes
+        "sparse_adagrad": ("hbm", 4 * nnz + 12 * U + B * F * D * 4 + U * (2 * D * e + 2 * state_row)),
+        "seg_reduce_long": ("hbm", 0),
+        # K shard gradients read once, fp32 weights and state read and written, both bf16 copies
+        "dense_adagrad": ("hbm", P * ((K + 4) * 4 + (4 if cfg.gemm_dtype == "bf16" else 0))),
     }
     return out
 
@@ -70,7 +73,7 @@ def run_ranking(args, cfg_id):
                         device=dev)
     params = torch.from_numpy(wl.make_mlp_params(cfg)).to(dev)
     pstate = torch.zeros_like(params)
-    nb = 8
+    nb = 8 if cfg.batch * cfg.num_fields < (1 << 20) else 2   # resident batches that are rotated
     batches = [wl.make_batch(cfg, i) for i in range(nb)]
     max_nnz = max(int(b.field_ptr[-1]) for b in batches)
     model = A.model_from_config(cfg, max_nnz=max_nnz)
@@ -252,7 +255,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:

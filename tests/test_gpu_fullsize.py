@@ -59,6 +59,7 @@ def run_fullsize(cfg, oracle_shards=None, check_rows=200_000):
     ctx.worker_step_all(loss)
     ctx.aggregate()
     torch.cuda.synchronize()
+    print(f"[{cfg.name}] GPU iteration done; oracle on the touched rows", flush=True)
 
     # ---- oracle on the touched rows
     model, tabs, cb, uniq = compact_problem(cfg, batch)
@@ -77,11 +78,15 @@ def run_fullsize(cfg, oracle_shards=None, check_rows=200_000):
         assert abs(gl[k] - r.loss) <= tol * abs(r.loss)
         assert_close(dense.cpu().numpy(), flat_dense_grad(cfg, r.dW, r.db), tol, f"dense gradient, shard {k}", mt)
         assert_close(dx.cpu().numpy(), r.dx, tol, f"d loss / d pooled, shard {k}", mt)
+    print(f"[{cfg.name}] per-shard parity done", flush=True)
     full = oracle_shards is None
     if full:
         agg = oracle.aggregate(model, cb, [res[k] for k in range(K)])
         assert_close(ctx.view_dense_grad().cpu().numpy(), flat_dense_grad(cfg, agg.dW, agg.db), tol,
                      "aggregated dense gradient", mt)
+    else:
+        sub = oracle.aggregate(model, cb, [res[k] for k in which])
+        sub_scale = sum(shards[k][1] for k in which) / cfg.batch
     Gs = []
     for f in range(F):
         u, so, ss, G = ctx.view_coalesced(f)
@@ -93,11 +98,20 @@ def run_fullsize(cfg, oracle_shards=None, check_rows=200_000):
         Gs.append(G.cpu().numpy())
         if full:
             assert_close(Gs[-1], agg.G[f], tol, f"coalesced gradient, field {f}", mt)
+        else:
+            # rows that only the oracle's shards look up: their coalesced gradient is the
+            # subset aggregate scaled by (samples of the subset) / B
+            su = sub.unique_ids[f]
+            only = np.diff(sub.seg_offsets[f]) == counts[su]
+            assert only.sum() > 0
+            assert_close(Gs[-1][su[only]], sub.G[f][only] * sub_scale, tol,
+                         f"coalesced gradient of rows private to the oracle's shards, field {f}", mt)
         if f < 3:  # grouping of the lookups: samples of every run, ascending
             ss = ss.cpu().numpy()
             sample = np.repeat(np.arange(cfg.batch), np.diff(batch.offsets[f]))
             order = np.lexsort((sample, cb.field_ids(f)))
             assert np.array_equal(ss, sample[order]), f"grouping of lookups, field {f}"
+    print(f"[{cfg.name}] aggregation parity done", flush=True)
     ctx.apply_update()
     torch.cuda.synchronize()
     # ---- update: the oracle's Adagrad rule applied to the GPU's coalesced gradient, on every
@@ -114,9 +128,13 @@ def run_fullsize(cfg, oracle_shards=None, check_rows=200_000):
         if cfg.table_dtype == "f32":
             assert_close(got - t0, p1 - t0, TOL32, f"Adagrad step on the GPU's G, field {f}")
         else:
-            gb = wl.f32_to_bf16_bits(got).astype(np.int64)
-            wb = wl.f32_to_bf16_bits(oracle.round_bf16(p1).astype(np.float32)).astype(np.int64)
-            assert np.abs(gb - wb).max() <= 1 and np.mean(gb != wb) < 0.01, f"bf16 write-back, field {f}"
+            # the stored bf16 value is the rounding of the oracle's fp64 result, or its bf16
+            # neighbour when the fp32 arithmetic lands on the other side of a rounding
+            # boundary (rare); where the step cancels the parameter the slack is absolute
+            want = oracle.round_bf16(p1)
+            diff = np.abs(got - want)
+            ok = (diff <= 2.0 ** -7 * np.maximum(np.abs(want), np.abs(got))) | (diff <= TOL32 * np.abs(t0))
+            assert ok.all() and np.mean(got != want) < 0.01, f"bf16 write-back, field {f}"
         assert_close(got_s, s1, TOL32, f"accumulator, field {f}")
         near = np.unique(np.clip(np.concatenate([u - 1, u + 1, rng.integers(0, R, check_rows // F)]), 0, R - 1))
         near = np.setdiff1d(near, u)
@@ -143,6 +161,14 @@ def test_config2_full_size():
 
 def test_config3_heterogeneous_shards_full_size():
     run_fullsize(wl.CONFIGS[3])
+
+
+def test_config4_bf16_tables_rowwise_state_full_size():
+    """128 GB of bf16 tables, one Adagrad accumulator per row, 41.8 M lookups per iteration.
+    The oracle runs four of the sixteen shards (per-shard gradients, and the coalesced
+    gradient of every row that only those shards touch); structure and update are checked
+    on all rows."""
+    run_fullsize(wl.CONFIGS[4], check_rows=100_000)
 
 
 def test_config5_dense_adam_full_size_sampled():
