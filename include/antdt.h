@@ -155,20 +155,24 @@ int antdt_worker_step(antdt_ctx* ctx, int32_t k, float* loss_out, void* stream);
 int antdt_worker_step_all(antdt_ctx* ctx, float* loss_out, void* stream);
 
 /*
- * Server-side aggregation of the pushed gradients (Section II: "the servers aggregate the
- * local gradients from all workers") of the included shards, weights w_k = B_k / sum of the
- * included B_k:
+ * Server-side aggregation of the pushed gradients (Section II: the servers combine the
+ * workers' gradients) of the included shards, weights w_k = B_k / sum of the included B_k:
  *   dense   g = sum_k w_k g_k;
  *   sparse  per field: the lookups of the included shards are sorted by row id; the distinct
  *           ids ascending (unique_ids), the start of each id's run (seg_offsets) and
  *           G[u, :] = sum over the run of w_k(sample) * d loss_k / d pooled[sample, field].
- * shard_mask: HOST uint8 [K], 0 = shard left out (its worker_step need not have run); NULL = all.
+ * shard_mask: HOST uint8 [K], 0 = shard left out, as when the servers disregard the gradients
+ * of the slowest workers (the backup-workers baseline, Section VII-A.3): its worker_step need
+ * not have run, its lookups are not coalesced and the weights renormalise over the others;
+ * NULL = all.  With a mask that leaves out a non-empty shard the call waits for `stream` once
+ * (it reads the per-field lookup counts of the remaining shards back to plan the sort);
+ * without one it only enqueues.
  * Requires worker_step for every included shard since the last set_batch / apply_update.
  */
 int antdt_aggregate(antdt_ctx* ctx, const uint8_t* shard_mask, void* stream);
 
 /*
- * Parameter update (Section II: "update the parameters"): Adagrad with the aggregated
+ * Parameter update (Section II: the servers update the parameters): Adagrad with the aggregated
  * gradient, S += g^2 (row-wise state: S[r] += mean_d g[r,d]^2), p -= lr * g / (sqrt(S) + eps),
  * on the rows listed by the last aggregate only and on all MLP parameters; bf16 tables are
  * written back round-to-nearest-even; bf16 operand copies of the MLP weights are refreshed.

@@ -5,11 +5,11 @@ inputs arrive as the float32 / bf16 values the caller stores and results that
 are *stored* (updated parameters and optimizer state) are rounded once to the
 storage type.
 
-Worker side (Section II: "worker i calculates its local gradient based on the
-local batch B_i and pushes it"): sum-pooled embedding bags, an MLP with ReLU
+Worker side (Section II, problem formulation: each worker computes a gradient on
+its own local batch B_i and pushes it to the servers): sum-pooled embedding bags, an MLP with ReLU
 hidden layers and one logit, mean binary cross-entropy over the shard.
-Server side (Section II: "the servers aggregate the local gradients from all
-workers and update the parameters"): gradients of the included shards are
+Server side (Section II: the servers combine the gradients pushed by all workers
+and then update the parameters): gradients of the included shards are
 averaged with weights B_k / sum B_k (the only weights that keep the update
 independent of how the fixed global batch is split, cf. the constraint
 sum_i B_i = B of Eq. 1), duplicate row ids are coalesced, and Adagrad is

@@ -1,10 +1,10 @@
-// Server-side coalescing of the pushed sparse gradients (Section II: "the servers
-// aggregate the local gradients from all workers"): per field, a stable LSD radix
+// Server-side coalescing of the pushed sparse gradients (Section II: the servers combine
+// the gradients of all workers): per field, a stable LSD radix
 // sort of (row id, sample index) pairs, detection of the runs of equal ids
 // (unique ids + segment offsets), and the weighted segmented reduction
 //   G[u, :] = sum over the run of w(sample) * dX[sample, field slice].
 // No floating-point atomics are used, so the sums are bitwise repeatable.  The reduction can
-// apply the row-sparse Adagrad step of each row at once (Section II: "update the parameters").
+// apply the row-sparse Adagrad step of each row at once (the parameter update of Section II).
 #include "common.h"
 
 namespace antdt {
@@ -164,6 +164,52 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
       keys_out[base + dst[i]] = key[i];
       pay_out[base + dst[i]] = pay[i];
     }
+  }
+}
+
+// ------------------------------------------------- leaving shards out
+// When the servers disregard the gradients of some workers (the backup-workers baseline of
+// Section VII-A.3), only the lookups of the remaining shards are coalesced.  A shard is a
+// contiguous range of samples, hence a contiguous range of every field's lookups: the ranges
+// of the included shards (weight != 0) are packed side by side, field after field.
+
+// cbase[f] = number of included lookups in the fields before f (cbase[F] = their total).
+__global__ __launch_bounds__(256) void mask_count_kernel(const int32_t* offsets, int64_t B, int F, ShardTab tab,
+                                                         int64_t* cbase) {
+  __shared__ int64_t cnt[ANTDT_MAX_FIELDS];
+  for (int f = threadIdx.x; f < F; f += 256) {
+    const int32_t* off = offsets + (int64_t)f * (B + 1);
+    int64_t c = 0;
+    for (int k = 0; k < tab.K; ++k)
+      if (tab.w[k] != 0.0f) c += off[tab.start[k] + tab.len[k]] - off[tab.start[k]];
+    cnt[f] = c;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int64_t run = 0;
+    for (int f = 0; f < F; ++f) {
+      cbase[f] = run;
+      run += cnt[f];
+    }
+    cbase[F] = run;
+  }
+}
+
+// Block (k, f) copies the ids and sample indices of shard k's lookups in field f.
+__global__ __launch_bounds__(256) void mask_pack_kernel(const int32_t* ids, const int32_t* lookup_sample,
+                                                        const int32_t* offsets, int64_t B, FieldPtr fp, ShardTab tab,
+                                                        const int64_t* cbase, int32_t* ids_out, int32_t* pay_out) {
+  const int k = blockIdx.x, f = blockIdx.y;
+  if (tab.w[k] == 0.0f) return;
+  const int32_t* off = offsets + (int64_t)f * (B + 1);
+  int64_t dst = cbase[f];
+  for (int q = 0; q < k; ++q)
+    if (tab.w[q] != 0.0f) dst += off[tab.start[q] + tab.len[q]] - off[tab.start[q]];
+  const int64_t src = fp.p[f] + off[tab.start[k]];
+  const int n = off[tab.start[k] + tab.len[k]] - off[tab.start[k]];
+  for (int i = threadIdx.x; i < n; i += 256) {
+    ids_out[dst + i] = ids[src + i];
+    pay_out[dst + i] = lookup_sample[src + i];
   }
 }
 
@@ -517,6 +563,15 @@ hipError_t launch_segments(const SegArgs& a, const FieldPtr& fp, const TileBase&
     ProfScope ps(prof, KID_SEG_EMIT, s);
     hipLaunchKernelGGL(seg_emit_kernel, grid, dim3(SORT_THREADS), 0, s, a, fp, tb);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_mask_pack(const int32_t* ids, const int32_t* lookup_sample, const int32_t* offsets, int64_t B, int F,
+                            const FieldPtr& fp, const ShardTab& tab, int64_t* cbase, int32_t* ids_out,
+                            int32_t* pay_out, hipStream_t s) {
+  hipLaunchKernelGGL(mask_count_kernel, dim3(1), dim3(256), 0, s, offsets, B, F, tab, cbase);
+  hipLaunchKernelGGL(mask_pack_kernel, dim3(tab.K, F), dim3(256), 0, s, ids, lookup_sample, offsets, B, fp, tab, cbase,
+                     ids_out, pay_out);
   return hipGetLastError();
 }
 

@@ -122,6 +122,12 @@ struct antdt_ctx {
   FieldPtr fp;
   TileBase tb;
   int max_tiles = 0, total_tiles = 0;
+  // the lookups that the current aggregation coalesces: all of the batch (the four above), or
+  // the packed lookups of the included shards when some are left out
+  FieldPtr afp;
+  TileBase atb;
+  int amax_tiles = 0, atotal_tiles = 0;
+  int64_t* cbase = nullptr;
   // shards
   ShardTab tab;
   bool have_shards = false;
@@ -201,6 +207,7 @@ static size_t carve(antdt_ctx* c, char* base) {
   c->ufield = (int32_t*)take((size_t)N * 4);
   c->segabs = (int32_t*)take((size_t)(N + 1) * 4);
   c->counters = (int32_t*)take(8);
+  c->cbase = (int64_t*)take((size_t)(ANTDT_MAX_FIELDS + 1) * 8);
   c->long_seg = (int32_t*)take((size_t)c->long_cap * 12);
   c->items = (int32_t*)take((size_t)c->item_cap * 8);
   c->partial = (float*)take((size_t)c->item_cap * m.dim * 4);
@@ -356,6 +363,26 @@ int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params
   return refresh_bf16_weights(c, (hipStream_t)stream);
 }
 
+// Tile decomposition of per-field lookup ranges (4096 keys per tile).
+static void plan_tiles(int F, const FieldPtr& fp, TileBase& tb, int& max_tiles, int& total_tiles) {
+  memset(&tb, 0, sizeof(tb));
+  max_tiles = 0;
+  for (int f = 0; f < F; ++f) {
+    const int tiles = (int)((fp.p[f + 1] - fp.p[f] + 4095) / 4096);
+    tb.t[f + 1] = tb.t[f] + tiles;
+    if (tiles > max_tiles) max_tiles = tiles;
+  }
+  for (int f = F + 1; f <= ANTDT_MAX_FIELDS; ++f) tb.t[f] = tb.t[F];
+  total_tiles = tb.t[F];
+}
+
+static void coalesce_whole_batch(antdt_ctx* c) {
+  c->afp = c->fp;
+  c->atb = c->tb;
+  c->amax_tiles = c->max_tiles;
+  c->atotal_tiles = c->total_tiles;
+}
+
 int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, const int32_t* offsets,
                     const float* dense, const float* labels, int64_t B, void* stream) {
   if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_batch: null context");
@@ -370,19 +397,10 @@ int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, 
   if (field_ptr[F] > c->m.max_nnz) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: more lookups than max_nnz");
   if (field_ptr[F] > 0 && !ids) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: null ids");
   memset(&c->fp, 0, sizeof(c->fp));
-  memset(&c->tb, 0, sizeof(c->tb));
-  c->max_tiles = 0;
-  for (int f = 0; f < F; ++f) {
-    c->fp.p[f + 1] = field_ptr[f + 1];
-    const int tiles = (int)((field_ptr[f + 1] - field_ptr[f] + 4095) / 4096);
-    c->tb.t[f + 1] = c->tb.t[f] + tiles;
-    if (tiles > c->max_tiles) c->max_tiles = tiles;
-  }
-  for (int f = F + 1; f <= ANTDT_MAX_FIELDS; ++f) {
-    c->fp.p[f] = c->fp.p[F];
-    c->tb.t[f] = c->tb.t[F];
-  }
-  c->total_tiles = c->tb.t[F];
+  for (int f = 0; f < F; ++f) c->fp.p[f + 1] = field_ptr[f + 1];
+  for (int f = F + 1; f <= ANTDT_MAX_FIELDS; ++f) c->fp.p[f] = c->fp.p[F];
+  plan_tiles(F, c->fp, c->tb, c->max_tiles, c->total_tiles);
+  coalesce_whole_batch(c);
   c->ids = ids;
   c->offsets = offsets;
   c->dense = dense;
@@ -467,8 +485,8 @@ static void fill_seg_args(antdt_ctx* c, SegArgs& a) {
   a.segabs = c->segabs; a.segoff = c->segoff; a.sample_w = c->sample_w; a.counters = c->counters;
   a.long_seg = c->long_seg; a.items = c->items; a.partial = c->partial;
   a.G = c->G; a.dx = c->dx; a.lddx = c->FD;
-  a.F = m.num_fields; a.D = m.dim; a.B = (int32_t)c->B; a.max_tiles = c->max_tiles;
-  a.total_tiles = c->total_tiles; a.long_threshold = c->long_threshold; a.chunk = c->chunk;
+  a.F = m.num_fields; a.D = m.dim; a.B = (int32_t)c->B; a.max_tiles = c->amax_tiles;
+  a.total_tiles = c->atotal_tiles; a.long_threshold = c->long_threshold; a.chunk = c->chunk;
   a.long_cap = (int32_t)c->long_cap; a.item_cap = (int32_t)c->item_cap;
   a.tables = c->tables; a.state = c->table_state; a.R = m.rows_per_field; a.lr = m.lr; a.eps = m.eps;
   a.table_bf16 = m.table_dtype == ANTDT_BF16; a.rowwise = m.adagrad_state == ANTDT_STATE_ROWWISE;
@@ -491,23 +509,23 @@ static void set_weights(antdt_ctx* c) {
 
 // Sort the lookups by row id, find the runs, and fill the per-sample weights: everything of
 // the server side that depends only on the batch's ids and on the shard weights.
-static int build_coalescing(antdt_ctx* c, hipStream_t s) {
+static int build_coalescing(antdt_ctx* c, const int32_t* ids, const int32_t* pay0, hipStream_t s) {
   Profiler* pr = prof_of(c);
   const antdt_model& m = c->m;
   SortPlan pl;
   pl.F = m.num_fields; pl.B = (int32_t)c->B; pl.passes = c->sort_passes; pl.radix_bits = c->radix_bits;
-  pl.max_tiles = c->max_tiles; pl.total_tiles = c->total_tiles;
+  pl.max_tiles = c->amax_tiles; pl.total_tiles = c->atotal_tiles;
   SortBuffers sb;
-  sb.ids = c->ids; sb.offsets = c->offsets;
+  sb.ids = ids; sb.offsets = c->offsets;
   sb.key[0] = c->key[0]; sb.key[1] = c->key[1]; sb.pay[0] = c->pay[0]; sb.pay[1] = c->pay[1];
   sb.hist = c->hist;
   sb.digit_base = c->digit_base;
-  sb.pay0 = c->lookup_sample;
-  for (int p = 0; p < pl.passes; ++p) HIP_TRY(c, launch_sort_pass(pl, sb, p, c->fp, c->tb, pr, s));
+  sb.pay0 = pay0;
+  for (int p = 0; p < pl.passes; ++p) HIP_TRY(c, launch_sort_pass(pl, sb, p, c->afp, c->atb, pr, s));
   c->sorted_buf = (pl.passes - 1) & 1;
   SegArgs a;
   fill_seg_args(c, a);
-  HIP_TRY(c, launch_segments(a, c->fp, c->tb, c->tab, pr, s));
+  HIP_TRY(c, launch_segments(a, c->afp, c->atb, c->tab, pr, s));
   return ANTDT_OK;
 }
 
@@ -545,7 +563,8 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     set_weights(c);
     HIP_TRY(c, hipEventRecord(c->ev_fork, s));
     HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
-    const int rc = build_coalescing(c, c->side);
+    coalesce_whole_batch(c);
+    const int rc = build_coalescing(c, c->ids, c->lookup_sample, c->side);
     if (rc) return rc;
     HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
     c->presorted = true;
@@ -707,18 +726,40 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
     if (c->included[k]) {
       if (c->tab.len[k] > 0 && !c->stepped[k])
         return fail(c, ANTDT_BAD_STATE, "antdt_aggregate: an included shard has no worker_step result");
-    } else if (c->tab.len[k] > 0) {
-      return fail(c, ANTDT_UNSUPPORTED, "antdt_aggregate: leaving out a non-empty shard is not implemented");
     }
   }
-  bool all = true;
-  for (int k = 0; k < K; ++k) all = all && c->included[k];
+  bool all = true;  // leaving out an empty shard changes nothing
+  for (int k = 0; k < K; ++k) all = all && (c->included[k] || c->tab.len[k] == 0);
+  if (c->presorted) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
   if (c->presorted && all) {
     // the batched worker step already built the structure on the side stream
-    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
-  } else {
+  } else if (all) {
     set_weights(c);
-    const int rc = build_coalescing(c, s);
+    coalesce_whole_batch(c);
+    const int rc = build_coalescing(c, c->ids, c->lookup_sample, s);
+    if (rc) return rc;
+  } else {
+    // Some shards are left out: pack the lookups of the others (the unique-id buffers serve as
+    // staging; the sort has consumed them before the runs are emitted there), fetch the
+    // per-field counts (the one place where the host waits for the stream) and coalesce those.
+    set_weights(c);
+    const int F = c->m.num_fields;
+    int32_t* ids_in = c->uniq;
+    int32_t* pay_in = c->ufield;
+    HIP_TRY(c, launch_mask_pack(c->ids, c->lookup_sample, c->offsets, c->B, F, c->fp, c->tab, c->cbase, ids_in,
+                                pay_in, s));
+    int64_t cb[ANTDT_MAX_FIELDS + 1];
+    HIP_TRY(c, hipMemcpyAsync(cb, c->cbase, (size_t)(F + 1) * 8, hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    memset(&c->afp, 0, sizeof(c->afp));
+    for (int f = 0; f <= F; ++f) {
+      if (cb[f] < 0 || cb[f] > c->fp.p[F] || (f > 0 && cb[f] < cb[f - 1]))
+        return fail(c, ANTDT_INVALID_ARG, "antdt_aggregate: offsets of the batch are not monotone");
+      c->afp.p[f] = cb[f];
+    }
+    for (int f = F + 1; f <= ANTDT_MAX_FIELDS; ++f) c->afp.p[f] = c->afp.p[F];
+    plan_tiles(F, c->afp, c->atb, c->amax_tiles, c->atotal_tiles);
+    const int rc = build_coalescing(c, ids_in, pay_in, s);
     if (rc) return rc;
   }
   c->presorted = false;
@@ -742,7 +783,7 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
       const int rc = reset_queues(c, s);
       if (rc) return rc;
     }
-    HIP_TRY(c, launch_seg_reduce(a, c->fp.p[m.num_fields], pr, s));
+    HIP_TRY(c, launch_seg_reduce(a, c->afp.p[m.num_fields], pr, s));
   }
   {
     DenseAdagradArgs a;
@@ -857,7 +898,7 @@ int antdt_view_coalesced(antdt_ctx* c, int32_t f, const int32_t** unique_ids, co
     SegArgs a;
     fill_seg_args(c, a);
     a.update = 0;
-    HIP_TRY(c, launch_seg_reduce(a, c->fp.p[c->m.num_fields], prof_of(c), (hipStream_t)stream));
+    HIP_TRY(c, launch_seg_reduce(a, c->afp.p[c->m.num_fields], prof_of(c), (hipStream_t)stream));
     c->g_valid = true;
   }
   int32_t ub[2];
@@ -865,9 +906,9 @@ int antdt_view_coalesced(antdt_ctx* c, int32_t f, const int32_t** unique_ids, co
   HIP_TRY(c, hipStreamSynchronize((hipStream_t)stream));
   *unique_ids = c->uniq + ub[0];
   *seg_offsets = c->segoff + ub[0] + f;
-  *seg_samples = c->pay[c->sorted_buf] + c->fp.p[f];
+  *seg_samples = c->pay[c->sorted_buf] + c->afp.p[f];
   *num_unique = ub[1] - ub[0];
-  *nnz = c->fp.p[f + 1] - c->fp.p[f];
+  *nnz = c->afp.p[f + 1] - c->afp.p[f];
   *G = c->G + (int64_t)ub[0] * c->m.dim;
   return ANTDT_OK;
 }

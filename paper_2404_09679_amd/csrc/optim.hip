@@ -1,5 +1,5 @@
-// Server-side dense aggregation and the parameter updates (Section II: "the
-// servers aggregate the local gradients ... and update the parameters").
+// Server-side dense aggregation and the parameter updates (Section II: the servers
+// combine the workers' gradients, then update the parameters).
 // All of these stream through memory once: they are bound by HBM bandwidth.
 #include "common.h"
 
