@@ -205,6 +205,55 @@ def cpu_baseline(cfg, batch):
                       "same batch), numpy float64, tables restricted to the touched rows"}
 
 
+def run_batch_sweep(args):
+    """Batch processing time of one worker against its local batch size (the F(B_k) curve of
+    Section VI-B): worker_step of a single shard of B_k samples of the config-2 workload, timed
+    with events.  The saturation batch is the largest B_k whose time is within 10 % of the
+    smallest batch's: below it a smaller batch no longer shortens the step."""
+    import numpy as np
+    import torch
+
+    import paper_2404_09679_amd as A
+    import workload as wl
+
+    cfg = wl.CONFIGS[2]
+    dev = "cuda:0"
+    F, R, D = cfg.num_fields, cfg.rows_per_field, cfg.dim
+    tables = torch.empty((F * R, D), dtype=torch.float32, device=dev)
+    A.fill_tables(tables, F, R, D, 0.05)
+    state = torch.zeros((F * R, D), dtype=torch.float32, device=dev)
+    params = torch.from_numpy(wl.make_mlp_params(cfg)).to(dev)
+    pstate = torch.zeros_like(params)
+    b = wl.make_batch(cfg, 0)
+    ctx = A.Context(A.model_from_config(cfg, max_nnz=int(b.field_ptr[-1])))
+    ctx.bind(tables, state, params, pstate)
+    ctx.set_batch(torch.from_numpy(b.ids).to(dev), b.field_ptr, torch.from_numpy(b.offsets).to(dev),
+                  torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.labels).to(dev))
+    B = cfg.batch
+    curve = []
+    bk = 8
+    while bk <= B:
+        ctx.assign_shard(B, 2, sizes=[bk, B - bk])
+        for _ in range(args.warmup):
+            ctx.worker_step(0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            ctx.worker_step(0)
+        e1.record()
+        torch.cuda.synchronize()
+        curve.append([bk, e0.elapsed_time(e1) * 1e3 / args.steps])
+        bk *= 2
+    base = curve[0][1]
+    sat = max(bk for bk, us in curve if us <= 1.1 * base)
+    return {"metric": "worker batch processing time vs local batch size", "unit": "us", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "data": "synthetic",
+            "dtype": "bf16", "config": {"workload": f"configs[1] {cfg.name}: worker_step of one shard of B_k samples"},
+            "curve_us": curve, "saturation_batch": sat,
+            "samples_per_s": [[bk, bk / (us * 1e-6)] for bk, us in curve]}
+
+
 def run_dense(args):
     import numpy as np
     import torch
@@ -255,13 +304,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "batch-sweep"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the K workers are shards on that device); "
                  "use --gpus 1")
-    if args.workload == "cfg5":
+    if args.workload == "batch-sweep":
+        out = run_batch_sweep(args)
+    elif args.workload == "cfg5":
         out = run_dense(args)
     else:
         out = run_ranking(args, int(args.workload[3:]))

@@ -47,7 +47,8 @@ enum {
   ANTDT_BAD_STATE = -2,           /* call order violated (see each call) */
   ANTDT_WORKSPACE_TOO_SMALL = -3,
   ANTDT_HIP_ERROR = -4,           /* a HIP runtime call failed; message holds hipGetErrorString */
-  ANTDT_UNSUPPORTED = -5
+  ANTDT_UNSUPPORTED = -5,
+  ANTDT_INFEASIBLE = -6           /* a planning problem has no solution within its bounds */
 };
 
 enum { ANTDT_F32 = 0, ANTDT_BF16 = 1 };
@@ -179,6 +180,35 @@ int antdt_aggregate(antdt_ctx* ctx, const uint8_t* shard_mask, void* stream);
  * Requires antdt_aggregate.
  */
 int antdt_apply_update(antdt_ctx* ctx, void* stream);
+
+/*
+ * Plan for heterogeneous dedicated devices with gradient accumulation (Section VI-B, Eq. 4).
+ * There are k device types; type i has n[i] devices of measured speed v[i] (samples per unit
+ * of time).  Each device of type i computes C_i micro-batches of B_i samples in sequence
+ * before the synchronisation.  Finds integers minimising  max_i C_i * B_i / v[i]  subject to
+ *   sum_i n[i] * C_i * B_i = B,  bmin[i] <= B_i <= bmax[i],  cmin <= C_i <= cmax
+ * (bmin: the saturation batch below which the batch time no longer falls; bmax: the memory
+ * limit).  Exact: the counts are enumerated, the batch sizes found by bisection over the
+ * candidate optimum values with an exact reachability table.  Among optimal plans the one
+ * returned is unspecified.  All arrays HOST; B_out, C_out: [k]; z_out (optional): the optimum.
+ * Limits: k <= 8, B <= 2^24, cmax <= 64, (cmax-cmin+1)^k <= 262144.
+ * Returns ANTDT_INFEASIBLE when no plan satisfies the constraints.  Host only, no GPU work.
+ */
+int antdt_plan_accumulation(int64_t B, int32_t k, const int32_t* n, const double* v,
+                            const int64_t* bmin, const int64_t* bmax, int32_t cmin, int32_t cmax,
+                            int64_t* B_out, int32_t* C_out, double* z_out);
+
+/*
+ * The micro-batches of such a plan as shard sizes for antdt_assign_shard, device after device
+ * (type 0's devices first), C_i consecutive shards of B_i samples per device of type i.  A
+ * micro-batch is a shard: aggregating the shards with weights B_i / B equals accumulating each
+ * device's micro-batch gradients and weighting the device by its share of B.
+ * sizes_out, device_out (optional: index of the device a shard belongs to): HOST [cap];
+ * count_out: number of shards written.  INVALID_ARG when cap is too small.
+ */
+int antdt_expand_accumulation(int32_t k, const int32_t* n, const int64_t* B_i, const int32_t* C_i,
+                              int32_t cap, int64_t* sizes_out, int32_t* device_out,
+                              int32_t* count_out);
 
 /*
  * Dense data-parallel step on one device (Section II: the AllReduce variant drops the

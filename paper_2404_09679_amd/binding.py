@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libantdt_hip.so")
 
 MAX_LAYERS, MAX_FIELDS, MAX_SHARDS = 8, 128, 64
 F32, BF16 = 0, 1
+INFEASIBLE = -6
 ELEMENTWISE, ROWWISE = 0, 1
 
 EXPORTS = [
@@ -20,6 +21,7 @@ EXPORTS = [
     "antdt_aggregate", "antdt_apply_update", "antdt_dense_aggregate_adam", "antdt_fill_tables",
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
+    "antdt_plan_accumulation", "antdt_expand_accumulation",
 ]
 
 
@@ -41,7 +43,7 @@ class Model(C.Structure):
 
 def _load():
     if not os.path.exists(_LIB_PATH):
-        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2404_09679_amd.build` "
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2404_09679_amd/build.py` "
                           "(there is no CPU fallback)")
     lib = C.CDLL(_LIB_PATH)
     vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
@@ -71,6 +73,11 @@ def _load():
     lib.antdt_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double)]
     lib.antdt_kernel_name.argtypes = [i32]
     lib.antdt_kernel_name.restype = C.c_char_p
+    lib.antdt_plan_accumulation.argtypes = [i64, i32, C.POINTER(i32), C.POINTER(C.c_double), C.POINTER(i64),
+                                            C.POINTER(i64), i32, i32, C.POINTER(i64), C.POINTER(i32),
+                                            C.POINTER(C.c_double)]
+    lib.antdt_expand_accumulation.argtypes = [i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32), i32,
+                                              C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
     return lib
 
 
@@ -263,3 +270,31 @@ def fill_tables(tables: torch.Tensor, num_fields: int, rows_per_field: int, dim:
     rc = lib.antdt_fill_tables(_ptr(tables), dt, num_fields, rows_per_field, dim, scale, _stream())
     if rc:
         raise AntdtError(rc, lib.antdt_last_error(None).decode())
+
+
+def plan_accumulation(B: int, counts: Sequence[int], speeds: Sequence[float], bmin: Sequence[int],
+                      bmax: Sequence[int], cmin: int, cmax: int):
+    """Eq. 4 plan: returns (batch sizes B_i, accumulation counts C_i, optimum z), or None when
+    no plan satisfies the constraints."""
+    k = len(counts)
+    Bo, Co, z = (C.c_int64 * k)(), (C.c_int32 * k)(), C.c_double()
+    rc = lib.antdt_plan_accumulation(B, k, (C.c_int32 * k)(*counts), (C.c_double * k)(*speeds),
+                                     (C.c_int64 * k)(*bmin), (C.c_int64 * k)(*bmax), cmin, cmax, Bo, Co,
+                                     C.byref(z))
+    if rc == INFEASIBLE:
+        return None
+    if rc:
+        raise AntdtError(rc, lib.antdt_last_error(None).decode())
+    return list(Bo), list(Co), z.value
+
+
+def expand_accumulation(counts: Sequence[int], batch_sizes: Sequence[int], accum: Sequence[int]):
+    """Shard sizes (and the device index of each shard) of a plan, for Context.assign_shard."""
+    k = len(counts)
+    cap = sum(int(n) * int(c) for n, c in zip(counts, accum))
+    sizes, dev, cnt = (C.c_int64 * max(cap, 1))(), (C.c_int32 * max(cap, 1))(), C.c_int32()
+    rc = lib.antdt_expand_accumulation(k, (C.c_int32 * k)(*counts), (C.c_int64 * k)(*batch_sizes),
+                                       (C.c_int32 * k)(*accum), cap, sizes, dev, C.byref(cnt))
+    if rc:
+        raise AntdtError(rc, lib.antdt_last_error(None).decode())
+    return list(sizes)[:cnt.value], list(dev)[:cnt.value]

@@ -6,7 +6,11 @@
 
 #include "antdt.h"
 
+#include <string>
+
 namespace antdt {
+
+void set_last_error(const std::string& msg);  // message returned by antdt_last_error(NULL)
 
 typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
 

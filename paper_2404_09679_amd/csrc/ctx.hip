@@ -70,6 +70,10 @@ using namespace antdt;
 
 static thread_local std::string g_last_error;
 
+namespace antdt {
+void set_last_error(const std::string& msg) { g_last_error = msg; }
+}
+
 enum Stage { ST_CREATED = 0, ST_BOUND, ST_BATCH, ST_AGGREGATED };
 
 struct antdt_ctx {

@@ -213,6 +213,42 @@ def test_masked_then_full_aggregation_of_the_same_batch():
         assert len(masked[f]) <= len(u)
 
 
+def test_gradient_accumulation_plan_as_micro_batch_shards():
+    """Section VI-B: every device computes C_i micro-batches of B_i samples before the
+    synchronisation.  The GPU runs the plan's micro-batches as shards; the oracle runs one
+    shard per device (the union of its micro-batches): the aggregated gradients and the update
+    must agree, because accumulating a device's micro-batch gradients and weighting the device
+    by its share of B is the same weighted sum."""
+    import paper_2404_09679_amd as A
+    from gpu_helpers import GpuRun
+    from helpers import tables_as_f32
+    cfg = wl.CONFIGS[1]
+    counts, speeds = (1, 2), (1.0, 2.5)
+    plan = A.plan_accumulation(cfg.batch, counts, speeds, (16, 16), (64, 64), 1, 3)
+    assert plan is not None
+    Bi, Ci, z = plan
+    sizes, dev = A.expand_accumulation(counts, Bi, Ci)
+    assert sum(sizes) == cfg.batch and max(Ci) > 1
+    per_device = [sum(s for s, d in zip(sizes, dev) if d == i) for i in range(sum(counts))]
+    tables, state, flat, fstate, batch = make_inputs(cfg, nonzero_state=True)
+    t32 = tables_as_f32(cfg, tables)
+    model, res, agg, upd = oracle_iteration(cfg, t32, state, flat, fstate, batch, per_device)
+    run = GpuRun(cfg, tables, flat, state, fstate, max_batch=batch.batch, max_shards=len(sizes))
+    run.set_batch(batch)
+    run.iteration(sizes, batched=True)
+    assert_close(run.g_dense, flat_dense_grad(cfg, agg.dW, agg.db), TOL32, "aggregated dense gradient")
+    for f in range(cfg.num_fields):
+        u, so, ss, G = run.coalesced[f]
+        assert np.array_equal(u.astype(np.int64), agg.unique_ids[f])
+        assert np.array_equal(so.astype(np.int64), agg.seg_offsets[f])
+        assert_close(G, agg.G[f], TOL32, f"coalesced gradient, field {f}")
+    # the accumulated gradient of one device: its micro-batch gradients weighted by their sizes
+    first = [k for k, d in enumerate(dev) if d == 1]
+    acc = sum(sizes[k] * run.shard_out[k][1].astype(np.float64) for k in first) / per_device[1]
+    assert_close(acc, flat_dense_grad(cfg, res[1].dW, res[1].db), TOL32, "accumulated gradient of device 1")
+    assert rel_err(run.params.cpu().numpy(), flat_layers(cfg, upd.layers))[0] <= TOL32
+
+
 def test_single_layer_model():
     check_iteration(ONE_LAYER, ONE_LAYER.shard_sizes)
 

@@ -13,7 +13,7 @@ import oracle
 import workload as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-A = pytest.importorskip("paper_2404_09679_amd", reason="build the library first (python -m paper_2404_09679_amd.build)")
+A = pytest.importorskip("paper_2404_09679_amd", reason="build the library first (python paper_2404_09679_amd/build.py)")
 
 
 def test_library_exports_every_declared_symbol():
@@ -127,3 +127,64 @@ def test_assign_shard_speed_mode_large_batch():
                 assert max(n / v for n, v in zip(moved, speeds)) >= z - 1e-12
     # equal speeds reproduce the initial B/n split
     assert [n for _, n in ctx.assign_shard(4096, 8, speed=[2.5] * 8)] == [512] * 8
+
+
+# ------------------------------------------------------------------ Eq. 4: accumulation plan
+def _check_plan(B, counts, speeds, bmin, bmax, cmin, cmax):
+    from fractions import Fraction
+    want_z, want_plans = oracle.accumulation_plan_bruteforce(B, counts, speeds, bmin, bmax, cmin, cmax)
+    got = A.plan_accumulation(B, counts, speeds, bmin, bmax, cmin, cmax)
+    if want_z is None:
+        assert got is None
+        return None
+    assert got is not None, "a feasible problem was reported infeasible"
+    Bi, Ci, z = got
+    assert (tuple(Ci), tuple(Bi)) in want_plans, f"{(Ci, Bi)} is not among the optimal plans {want_plans}"
+    assert sum(n * c * b for n, c, b in zip(counts, Ci, Bi)) == B
+    assert abs(z - float(want_z)) <= 1e-12 * float(want_z)
+    assert max(Fraction(c * b) / Fraction(v) for c, b, v in zip(Ci, Bi, speeds)) == want_z
+    return got
+
+
+def test_accumulation_plan_worked_cases():
+    # one fast and one slow device: the fast one accumulates three micro-batches
+    Bi, Ci, z = _check_plan(32, (1, 1), (1.0, 3.0), (2, 2), (8, 8), 1, 3)
+    assert z == 8.0
+    assert _check_plan(5, (2,), (1.0,), (1,), (2,), 1, 1) is None           # 2*C*B = 5 has no solution
+    _check_plan(24, (2, 1), (1.0, 2.0), (1, 1), (24, 24), 1, 1)              # no accumulation: Eq. 3 with device counts
+    _check_plan(7, (1,), (0.3,), (1,), (7,), 1, 7)                           # one type: any C*B = 7
+
+
+def test_accumulation_plan_matches_enumeration_on_random_instances():
+    rng = np.random.default_rng(11)
+    feasible = 0
+    for _ in range(60):
+        k = int(rng.integers(1, 4))
+        counts = tuple(int(x) for x in rng.integers(1, 4, k))
+        speeds = tuple(float(x) for x in rng.choice([0.5, 1.0, 1.5, 2.0, 3.0, 0.7, 1.3], k))
+        bmin = tuple(int(x) for x in rng.integers(1, 4, k))
+        bmax = tuple(int(b + x) for b, x in zip(bmin, rng.integers(0, 6, k)))
+        cmin = int(rng.integers(1, 3))
+        cmax = cmin + int(rng.integers(0, 3))
+        B = int(rng.integers(1, 80))
+        if _check_plan(B, counts, speeds, bmin, bmax, cmin, cmax) is not None:
+            feasible += 1
+    assert feasible >= 10
+
+
+def test_accumulation_plan_rejects_bad_arguments():
+    with pytest.raises(A.AntdtError):
+        A.plan_accumulation(0, (1,), (1.0,), (1,), (2,), 1, 1)
+    with pytest.raises(A.AntdtError):
+        A.plan_accumulation(8, (1,), (-1.0,), (1,), (2,), 1, 1)
+    with pytest.raises(A.AntdtError):
+        A.plan_accumulation(8, (1,), (1.0,), (3,), (2,), 1, 1)
+    with pytest.raises(A.AntdtError):
+        A.plan_accumulation(8, (1,), (1.0,), (1,), (2,), 2, 1)
+
+
+def test_expand_accumulation_lists_micro_batches_device_by_device():
+    sizes, dev = A.expand_accumulation((2, 1), (4, 3), (2, 3))
+    assert sizes == [4, 4, 4, 4, 3, 3, 3]
+    assert dev == [0, 0, 1, 1, 2, 2, 2]
+    assert A.expand_accumulation((1,), (5,), (0,)) == ([], [])
