@@ -182,6 +182,13 @@ int antdt_aggregate(antdt_ctx* ctx, const uint8_t* shard_mask, void* stream);
 int antdt_apply_update(antdt_ctx* ctx, void* stream);
 
 /*
+ * Learning rate of the following antdt_apply_update calls (the ADJUST_LR global action of
+ * Table II changes it between iterations; the optimizer state is kept).  lr finite, >= 0.
+ * Host only.
+ */
+int antdt_set_lr(antdt_ctx* ctx, float lr);
+
+/*
  * Plan for heterogeneous dedicated devices with gradient accumulation (Section VI-B, Eq. 4).
  * There are k device types; type i has n[i] devices of measured speed v[i] (samples per unit
  * of time).  Each device of type i computes C_i micro-batches of B_i samples in sequence

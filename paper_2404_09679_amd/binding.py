@@ -21,7 +21,7 @@ EXPORTS = [
     "antdt_aggregate", "antdt_apply_update", "antdt_dense_aggregate_adam", "antdt_fill_tables",
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
-    "antdt_plan_accumulation", "antdt_expand_accumulation",
+    "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr",
 ]
 
 
@@ -73,6 +73,7 @@ def _load():
     lib.antdt_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double)]
     lib.antdt_kernel_name.argtypes = [i32]
     lib.antdt_kernel_name.restype = C.c_char_p
+    lib.antdt_set_lr.argtypes = [vp, f32]
     lib.antdt_plan_accumulation.argtypes = [i64, i32, C.POINTER(i32), C.POINTER(C.c_double), C.POINTER(i64),
                                             C.POINTER(i64), i32, i32, C.POINTER(i64), C.POINTER(i32),
                                             C.POINTER(C.c_double)]
@@ -194,6 +195,9 @@ class Context:
     def aggregate(self, shard_mask: Optional[Sequence[int]] = None):
         mk = (C.c_uint8 * len(shard_mask))(*[1 if v else 0 for v in shard_mask]) if shard_mask is not None else None
         self._check(lib.antdt_aggregate(self._h, mk, _stream()))
+
+    def set_lr(self, lr: float):
+        self._check(lib.antdt_set_lr(self._h, lr))
 
     def apply_update(self):
         self._check(lib.antdt_apply_update(self._h, _stream()))

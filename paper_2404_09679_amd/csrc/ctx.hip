@@ -773,6 +773,13 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
   return ANTDT_OK;
 }
 
+int antdt_set_lr(antdt_ctx* c, float lr) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_lr: null context");
+  if (!(lr >= 0.f) || !isfinite(lr)) return fail(c, ANTDT_INVALID_ARG, "antdt_set_lr: lr must be finite and >= 0");
+  c->m.lr = lr;
+  return ANTDT_OK;
+}
+
 int antdt_apply_update(antdt_ctx* c, void* stream) {
   if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_apply_update: null context");
   if (c->stage != ST_AGGREGATED) return fail(c, ANTDT_BAD_STATE, "antdt_apply_update: call antdt_aggregate first");

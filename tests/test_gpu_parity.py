@@ -249,6 +249,30 @@ def test_gradient_accumulation_plan_as_micro_batch_shards():
     assert rel_err(run.params.cpu().numpy(), flat_layers(cfg, upd.layers))[0] <= TOL32
 
 
+def test_learning_rate_change_between_iterations():
+    """ADJUST_LR (Table II): the next update uses the new rate, the accumulators carry on."""
+    from gpu_helpers import GpuRun
+    from helpers import tables_as_f32
+    cfg = wl.CONFIGS[1]
+    tables, state, flat, fstate, batch = make_inputs(cfg, nonzero_state=True)
+    cfg_half = wl.scaled(cfg, lr=cfg.lr * 0.25)
+    model, res, agg, upd = oracle_iteration(cfg_half, tables_as_f32(cfg, tables), state, flat, fstate, batch,
+                                            cfg.shard_sizes)
+    run = GpuRun(cfg, tables, flat, state, fstate, max_batch=batch.batch, max_shards=len(cfg.shard_sizes))
+    run.ctx.set_lr(cfg.lr * 0.25)
+    run.set_batch(batch)
+    run.iteration(cfg.shard_sizes)
+    p_new = run.params.cpu().numpy()
+    assert rel_err(p_new - flat, flat_layers(cfg, upd.layers) - flat)[0] <= TOL32
+    R = cfg.rows_per_field
+    new_tables = run.tables.cpu().numpy()
+    for f in range(cfg.num_fields):
+        u = agg.unique_ids[f]
+        assert rel_err(new_tables[f * R + u] - tables[f * R + u], upd.rows[f] - tables[f * R + u])[0] <= TOL32
+    with pytest.raises(Exception):
+        run.ctx.set_lr(float("nan"))
+
+
 def test_single_layer_model():
     check_iteration(ONE_LAYER, ONE_LAYER.shard_sizes)
 
