@@ -330,22 +330,23 @@ struct Row4 {
 };
 
 // g += w(sample) * dX[sample, field slice] over sorted entries [b, e) taken with stride `step`,
-// four entries in flight.
+// NF entries in flight (added in order).
+template <int NF = 4>
 __device__ __forceinline__ void accumulate_run(const SegArgs& a, const float* dxcol, int b, int e, int step, Row4& g) {
   int i = b;
-  for (; i + 3 * step < e; i += 4 * step) {
-    int s[4];
+  for (; i + (NF - 1) * step < e; i += NF * step) {
+    int s[NF];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) s[q] = min(max(a.pay[i + q * step], 0), a.B - 1);
-    float w[4];
-    float4 x[4];
+    for (int q = 0; q < NF; ++q) s[q] = min(max(a.pay[i + q * step], 0), a.B - 1);
+    float w[NF];
+    float4 x[NF];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < NF; ++q) {
       w[q] = a.sample_w[s[q]];
       x[q] = *reinterpret_cast<const float4*>(dxcol + (int64_t)s[q] * a.lddx);
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < NF; ++q) {
       g.v[0] = fmaf(w[q], x[q].x, g.v[0]);
       g.v[1] = fmaf(w[q], x[q].y, g.v[1]);
       g.v[2] = fmaf(w[q], x[q].z, g.v[2]);
@@ -501,8 +502,19 @@ __global__ __launch_bounds__(256) void seg_finish_kernel(SegArgs a) {
     float srow0 = 0.f;
     if (UPDATE) load_row<TT, ROWWISE>(a, row, c, p0, s0, srow0);
     Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
-    for (int q = 0; q < nch; ++q) {
-      const float4 v = *reinterpret_cast<const float4*>(a.partial + (int64_t)(base + q) * a.D + c * 4);
+    const float* part = a.partial + (int64_t)base * a.D + c * 4;
+    int q = 0;
+    for (; q + 3 < nch; q += 4) {  // four loads in flight, added in chunk order
+      float4 v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = *reinterpret_cast<const float4*>(part + (int64_t)(q + j) * a.D);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        gsum.v[0] += v[j].x; gsum.v[1] += v[j].y; gsum.v[2] += v[j].z; gsum.v[3] += v[j].w;
+      }
+    }
+    for (; q < nch; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)q * a.D);
       gsum.v[0] += v.x; gsum.v[1] += v.y; gsum.v[2] += v.z; gsum.v[3] += v.w;
     }
     if (UPDATE) adagrad_row<TT, ROWWISE>(a, row, c, lps, gsum, p0, s0, srow0);
