@@ -266,7 +266,9 @@ int antdt_view_coalesced(antdt_ctx* ctx, int32_t f, const int32_t** unique_ids,
 
 /*
  * Optional per-kernel timing with HIP events on the launch stream.  mode 0: off;
- * mode 1: every kernel class; mode 2: only the class `kernel_id`.  Timings accumulate until
+ * mode 1: every kernel class; mode 2: only the class `kernel_id`; mode 3: the classes whose bit
+ * is set in `kernel_id` read as a mask (bit i = class i).  The matrix products of a pass that
+ * are launched back to back share one pair of events.  Timings accumulate until
  * antdt_profile_read, which synchronises the recorded events and reports, per class, the
  * number of launches and their total duration in milliseconds, then resets.
  * antdt_kernel_name returns the class name (NULL past the last class).

@@ -67,12 +67,14 @@ enum KernelId {
   KID_DENSE_ADAGRAD,
   KID_ADAM,
   KID_TRANSPOSE,
+  KID_GEMM_BWD,
   KID_COUNT
 };
 
 struct Profiler;  // defined in ctx.hip
 void prof_begin(Profiler* p, int kid, hipStream_t s);
 void prof_end(Profiler* p, int kid, hipStream_t s);
+void prof_count(Profiler* p, int launches);  // launches covered by the open bracket (default 1)
 
 struct ProfScope {
   Profiler* p;
@@ -83,6 +85,15 @@ struct ProfScope {
   }
   ~ProfScope() {
     if (p) prof_end(p, kid, s);
+  }
+  // One bracket of events around several back-to-back launches: the bracket itself costs a few
+  // microseconds on the stream, which would swamp kernels of 10-20 us if each had its own.
+  void launches(int n) {
+    if (p) prof_count(p, n);
+  }
+  void close() {  // end the bracket before the scope does
+    if (p) prof_end(p, kid, s);
+    p = nullptr;
   }
 };
 

@@ -14,6 +14,7 @@ namespace antdt {
 struct ProfRec {
   hipEvent_t start, stop;
   int kid;
+  int n = 1;  // launches inside the bracket
 };
 struct Profiler {
   int mode = 0, sel = -1;
@@ -26,7 +27,7 @@ struct Profiler {
 
 void prof_begin(Profiler* p, int kid, hipStream_t s) {
   p->open = nullptr;
-  if (p->mode == 0 || (p->mode == 2 && kid != p->sel)) return;
+  if (p->mode == 0 || (p->mode == 2 && kid != p->sel) || (p->mode == 3 && !((p->sel >> kid) & 1))) return;
   ProfRec r;
   r.kid = kid;
   if (!p->pool.empty()) {
@@ -41,6 +42,9 @@ void prof_begin(Profiler* p, int kid, hipStream_t s) {
   p->recs.push_back(r);
   p->open = &p->recs.back();
 }
+void prof_count(Profiler* p, int launches) {
+  if (p->open) p->open->n = launches;
+}
 void prof_end(Profiler* p, int, hipStream_t s) {
   if (p->open) (void)hipEventRecord(p->open->stop, s);
   p->open = nullptr;
@@ -51,7 +55,7 @@ static void prof_drain(Profiler* p) {
     float ms = 0.f;
     if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
       p->total_ms[r.kid] += ms;
-      p->launches[r.kid] += 1;
+      p->launches[r.kid] += r.n;
     }
     p->pool.push_back({r.start, r.stop});
   }
@@ -62,7 +66,7 @@ static const char* kKernelNames[KID_COUNT] = {
     "pool",        "gemm_fwd",   "gemm_dgrad",     "gemm_wgrad",  "head",
     "head_reduce", "bias_grad",  "sort_hist",      "sort_scan",   "sort_scatter",
     "seg_heads",   "seg_scan",   "seg_emit",       "seg_reduce",  "seg_reduce_long",
-    "dense_agg",   "sparse_adagrad", "dense_adagrad", "adam", "transpose"};
+    "dense_agg",   "sparse_adagrad", "dense_adagrad", "adam", "transpose", "gemm_bwd"};
 
 }  // namespace antdt
 
@@ -578,6 +582,9 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
   auto weight = [&](int l) -> const void* {
     return c->act_bf16 ? (const void*)c->wb[l] : (const void*)(c->params + c->w_off[l]);
   };
+  // the matrix products of each pass are timed as one bracket when they run back to back
+  ProfScope fwd_scope(L > 1 ? pr : nullptr, KID_GEMM_FWD, s);
+  fwd_scope.launches(L - 1);
   for (int l = 0; l + 1 < L; ++l) {  // hidden layers
     GemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -594,9 +601,9 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       g.B = c->params + c->w_off[l]; g.ldb = c->width[l + 1]; g.b_kc = 0;
     }
     g.epi = EPI_BIAS_RELU; g.bf16_in = c->act_bf16; g.bf16_out = c->act_bf16;
-    ProfScope ps(pr, KID_GEMM_FWD, s);
     HIP_TRY(c, launch_gemm(g, tab, s));
   }
+  fwd_scope.close();
   {
     HeadArgs a;
     memset(&a, 0, sizeof(a));
@@ -645,6 +652,9 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       HIP_TRY(c, launch_transpose_bf16(t, s));
     }
   }
+  ProfScope bwd_scope(c->act_bf16 && L > 1 ? pr : nullptr, KID_GEMM_BWD, s);
+  bwd_scope.launches(2 * (L - 1));
+  Profiler* pr_each = c->act_bf16 ? nullptr : pr;  // the fp32 path has other kernels in between
   for (int l = L - 2; l >= 0; --l) {
     if (c->act_bf16) {
       // [dW_l ; db_l][k] = [act_l ; 1]^T dh_{l+1} over the shard's samples: both operands are the
@@ -658,7 +668,6 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       g.M = c->width[l] + 1; g.N = c->width[l + 1]; g.K = 0;
       g.epi = EPI_PLAIN; g.bf16_in = 1; g.bf16_out = 0;
       g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
-      ProfScope ps(pr, KID_GEMM_WGRAD, s);
       HIP_TRY(c, launch_gemm(g, tab, s));
     } else {
       {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
@@ -698,10 +707,11 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
         g.C = c->dx + s0 * c->FD; g.ldc = c->FD; g.N = c->FD;
         g.epi = EPI_PLAIN; g.bf16_out = 0;
       }
-      ProfScope ps(pr, KID_GEMM_DGRAD, s);
+      ProfScope ps(pr_each, KID_GEMM_DGRAD, s);
       HIP_TRY(c, launch_gemm(g, tab, s));
     }
   }
+  bwd_scope.close();
   for (int k = k0; k < k1; ++k) c->stepped[k] = true;
   if (c->stage == ST_AGGREGATED) c->stage = ST_BATCH;
   return ANTDT_OK;
@@ -926,7 +936,7 @@ int antdt_view_coalesced(antdt_ctx* c, int32_t f, const int32_t** unique_ids, co
 
 int antdt_profile(antdt_ctx* c, int32_t mode, int32_t kernel_id) {
   if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_profile: null context");
-  if (mode < 0 || mode > 2 || (mode == 2 && (kernel_id < 0 || kernel_id >= KID_COUNT)))
+  if (mode < 0 || mode > 3 || (mode == 2 && (kernel_id < 0 || kernel_id >= KID_COUNT)))
     return fail(c, ANTDT_INVALID_ARG, "antdt_profile: invalid mode or kernel id");
   c->prof.mode = mode;
   c->prof.sel = kernel_id;

@@ -1,0 +1,75 @@
+"""HBM traffic per kernel class and training step from rocprofv3 counter runs.
+
+    python paper_2404_09679_amd/pmc_summary.py <dir>
+
+<dir> holds four rocprofv3 --pmc outputs (csv), one counter each:
+    bench_FETCH_SIZE/ bench_WRITE_SIZE/   python3 bench.py --steps 40 --warmup 10 --no-cpu-baseline
+    copy_FETCH_SIZE/  copy_WRITE_SIZE/    python3 bench.py --workload copy-calibration --steps 10
+The counters are in KiB per dispatch.  They are scaled by what the same counter reads for the
+plain copy kernel (1 GiB read and 1 GiB written per launch): on this machine FETCH_SIZE reads
+half the bytes actually fetched.  Dispatches are walked in order; a step starts at the pooling
+kernel, matrix products before the loss kernel are the forward pass, those after it the
+backward pass.  The first five steps are dropped.
+"""
+import collections
+import csv
+import glob
+import sys
+
+
+def _rows(d):
+    path = glob.glob(f"{d}/**/*counter_collection.csv", recursive=True)[0]
+    rows = list(csv.DictReader(open(path)))
+    rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+    return rows
+
+
+def class_totals(rows):
+    out, cur, after_head = collections.defaultdict(list), None, False
+    for r in rows:
+        k, v = r["Kernel_Name"], float(r["Counter_Value"])
+        if "pool_tile" in k or "pool_kernel" in k:
+            if cur is not None:
+                for c, x in cur.items():
+                    out[c].append(x)
+            cur, after_head, cls = collections.defaultdict(float), False, "pool"
+        elif cur is None:
+            continue
+        elif "head_tile" in k or "head_kernel" in k:
+            after_head, cls = True, "head"
+        elif "head_reduce" in k:
+            cls = "head_reduce"
+        elif "gemm_" in k:
+            cls = "gemm_bwd" if after_head else "gemm_fwd"
+        elif "seg_reduce" in k:
+            cls = "sparse_adagrad"
+        elif "seg_chunk" in k or "seg_finish" in k:
+            cls = "seg_reduce_long"
+        elif "dense_adagrad" in k:
+            cls = "dense_adagrad"
+        elif "sort_" in k:
+            cls = "sort"
+        elif "seg_" in k:
+            cls = "segments"
+        else:
+            cls = "other"
+        cur[cls] += v
+    return {c: sum(x[5:]) / max(len(x[5:]), 1) for c, x in out.items()}
+
+
+def main(d):
+    fs = float(_rows(f"{d}/copy_FETCH_SIZE")[-1]["Counter_Value"])
+    ws = float(_rows(f"{d}/copy_WRITE_SIZE")[-1]["Counter_Value"])
+    fscale, wscale = 1048576.0 / fs, 1048576.0 / ws
+    print(f"copy kernel (1048576 KiB read, 1048576 KiB written): FETCH_SIZE {fs:.0f}, WRITE_SIZE {ws:.0f} "
+          f"-> scale factors {fscale:.3f} (fetch), {wscale:.3f} (write)")
+    f = class_totals(_rows(f"{d}/bench_FETCH_SIZE"))
+    w = class_totals(_rows(f"{d}/bench_WRITE_SIZE"))
+    print(f"{'class':18s} {'fetched MB':>11s} {'written MB':>11s} {'total MB':>10s}   per step, scaled")
+    for c in sorted(f):
+        fm, wm = f[c] * fscale * 1024 / 1e6, w.get(c, 0.0) * wscale * 1024 / 1e6
+        print(f"{c:18s} {fm:11.1f} {wm:11.1f} {fm + wm:10.1f}")
+
+
+if __name__ == "__main__":
+    main(sys.argv[1])
