@@ -259,7 +259,10 @@ int antdt_view_shard_grads(antdt_ctx* ctx, int32_t k, const float** dense, const
 int antdt_view_dense_grad(antdt_ctx* ctx, const float** g, void* stream);
 /* Coalesced sparse gradient of field f after antdt_aggregate: unique_ids int32 [U_f] ascending,
  * seg_offsets int32 [U_f + 1], seg_samples int32 [nnz_f] (global sample index of every sorted
- * lookup; inside a run ascending), G fp32 [U_f, D].  Synchronises `stream`. */
+ * lookup; inside a run ascending), G fp32 [U_f, D]; with a mask, of the included shards'
+ * lookups only.  G is written out on the first request (apply_update applies the same sums
+ * without storing them).  Valid between antdt_aggregate and antdt_apply_update (BAD_STATE
+ * otherwise).  Synchronises `stream`. */
 int antdt_view_coalesced(antdt_ctx* ctx, int32_t f, const int32_t** unique_ids,
                          const int32_t** seg_offsets, const int32_t** seg_samples,
                          int64_t* num_unique, int64_t* nnz, const float** G, void* stream);
