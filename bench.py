@@ -71,7 +71,7 @@ def _bytes_and_flops(cfg, stats, model):
         "pool": ("hbm", 4 * nnz + 4 * F * (B + 1) + U * D * e + B * ldx * es
                  + (B * ldx * 2 if cfg.gemm_dtype == "bf16" else 0) + 4 * nnz),
         "gemm_fwd": ("mfma", fwd),
-        "gemm_bwd": ("mfma", fwd + dgrad),     # weight gradients (same flops as forward) + data gradients
+        "gemm_bwd": ("mfma", dgrad),           # the data-gradient chain on the launch stream
         "gemm_dgrad": ("mfma", dgrad),
         "gemm_wgrad": ("mfma", fwd),
         "sort_hist": ("hbm", passes * 4 * nnz),
@@ -140,9 +140,10 @@ def run_ranking(args, cfg_id):
         n, ms = ctx.profile_read(kid)
         if n:
             per_class[name] = (n / max(args.warmup, 1), ms / max(args.warmup, 1))
-    # the kernels that build the coalescing structure run on the side stream beside the MLP:
-    # they are off the critical path, and events on two concurrent streams time them badly
-    side = {"sort_hist", "sort_scan", "sort_scatter", "seg_heads", "seg_scan", "seg_emit"}
+    # the kernels that build the coalescing structure and the weight-gradient products run on
+    # side streams beside the launch stream: they are off the critical path, and events on
+    # concurrent streams time them badly
+    side = {"sort_hist", "sort_scan", "sort_scatter", "seg_heads", "seg_scan", "seg_emit", "gemm_wgrad"}
     critical = {k: v for k, v in per_class.items() if k not in side} or per_class
     dominant = max(critical, key=lambda k: critical[k][1]) if critical else names[0]
     bits = max(1, int(np.ceil(np.log2(R))))

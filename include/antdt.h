@@ -250,7 +250,9 @@ int antdt_fill_tables(void* tables, int32_t dtype, int32_t num_fields, int64_t r
  * BF16); columns [0, F*D + num_dense) are meaningful. */
 int antdt_view_pooled(antdt_ctx* ctx, int32_t k, const void** x, int64_t* rows, int64_t* ld,
                       int32_t* dtype);
-/* Shard k's dense gradient (fp32, flat layout) and d loss_k / d pooled (fp32 [B_k, ld_dx]). */
+/* Shard k's dense gradient (fp32, flat layout) and d loss_k / d pooled (fp32 [B_k, ld_dx]).
+ * Waits (on the host) for the library's own stream that writes the weight gradients; the
+ * caller still synchronises the stream it passed to antdt_worker_step before reading. */
 int antdt_view_shard_grads(antdt_ctx* ctx, int32_t k, const float** dense, const float** dx,
                            int64_t* ld_dx);
 /* Aggregated dense gradient (fp32, flat layout), written out on this request (apply_update

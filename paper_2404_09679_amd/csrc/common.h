@@ -72,27 +72,26 @@ enum KernelId {
 };
 
 struct Profiler;  // defined in ctx.hip
-void prof_begin(Profiler* p, int kid, hipStream_t s);
-void prof_end(Profiler* p, int kid, hipStream_t s);
-void prof_count(Profiler* p, int launches);  // launches covered by the open bracket (default 1)
+int prof_begin(Profiler* p, int kid, hipStream_t s);   // returns the bracket's index, -1 if not timed
+void prof_end(Profiler* p, int idx, hipStream_t s);
+void prof_count(Profiler* p, int idx, int launches);   // launches covered by the bracket (default 1)
 
+// A pair of events on stream `s` around the launches made while the scope is open.
 struct ProfScope {
   Profiler* p;
-  int kid;
+  int idx = -1;
   hipStream_t s;
-  ProfScope(Profiler* p_, int kid_, hipStream_t s_) : p(p_), kid(kid_), s(s_) {
-    if (p) prof_begin(p, kid, s);
+  ProfScope(Profiler* p_, int kid, hipStream_t s_) : p(p_), s(s_) {
+    if (p) idx = prof_begin(p, kid, s);
   }
-  ~ProfScope() {
-    if (p) prof_end(p, kid, s);
-  }
-  // One bracket of events around several back-to-back launches: the bracket itself costs a few
+  ~ProfScope() { close(); }
+  // One bracket around several back-to-back launches: the bracket itself costs a few
   // microseconds on the stream, which would swamp kernels of 10-20 us if each had its own.
   void launches(int n) {
-    if (p) prof_count(p, n);
+    if (p && idx >= 0) prof_count(p, idx, n);
   }
   void close() {  // end the bracket before the scope does
-    if (p) prof_end(p, kid, s);
+    if (p && idx >= 0) prof_end(p, idx, s);
     p = nullptr;
   }
 };

@@ -15,6 +15,7 @@ struct ProfRec {
   hipEvent_t start, stop;
   int kid;
   int n = 1;  // launches inside the bracket
+  bool closed = false;
 };
 struct Profiler {
   int mode = 0, sel = -1;
@@ -22,12 +23,10 @@ struct Profiler {
   std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
   double total_ms[KID_COUNT] = {};
   int64_t launches[KID_COUNT] = {};
-  ProfRec* open = nullptr;
 };
 
-void prof_begin(Profiler* p, int kid, hipStream_t s) {
-  p->open = nullptr;
-  if (p->mode == 0 || (p->mode == 2 && kid != p->sel) || (p->mode == 3 && !((p->sel >> kid) & 1))) return;
+int prof_begin(Profiler* p, int kid, hipStream_t s) {
+  if (p->mode == 0 || (p->mode == 2 && kid != p->sel) || (p->mode == 3 && !((p->sel >> kid) & 1))) return -1;
   ProfRec r;
   r.kid = kid;
   if (!p->pool.empty()) {
@@ -35,25 +34,24 @@ void prof_begin(Profiler* p, int kid, hipStream_t s) {
     r.stop = p->pool.back().second;
     p->pool.pop_back();
   } else {
-    if (hipEventCreate(&r.start) != hipSuccess) return;
-    if (hipEventCreate(&r.stop) != hipSuccess) return;
+    if (hipEventCreate(&r.start) != hipSuccess) return -1;
+    if (hipEventCreate(&r.stop) != hipSuccess) return -1;
   }
   (void)hipEventRecord(r.start, s);
   p->recs.push_back(r);
-  p->open = &p->recs.back();
+  return (int)p->recs.size() - 1;
 }
-void prof_count(Profiler* p, int launches) {
-  if (p->open) p->open->n = launches;
-}
-void prof_end(Profiler* p, int, hipStream_t s) {
-  if (p->open) (void)hipEventRecord(p->open->stop, s);
-  p->open = nullptr;
+void prof_count(Profiler* p, int idx, int launches) { p->recs[idx].n = launches; }
+void prof_end(Profiler* p, int idx, hipStream_t s) {
+  p->recs[idx].closed = true;
+  (void)hipEventRecord(p->recs[idx].stop, s);
 }
 
 static void prof_drain(Profiler* p) {
   for (auto& r : p->recs) {
     float ms = 0.f;
-    if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+    if (r.closed && hipEventSynchronize(r.stop) == hipSuccess &&
+        hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
       p->total_ms[r.kid] += ms;
       p->launches[r.kid] += r.n;
     }
@@ -146,6 +144,12 @@ struct antdt_ctx {
   // side stream on which the coalescing structure of a batch is built while the MLP runs
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  // second side stream: the weight-gradient products, which nothing needs before the dense
+  // update, run there beside the data-gradient chain and the sparse reduction
+  hipStream_t wside = nullptr;
+  hipEvent_t ev_dh[ANTDT_MAX_LAYERS + 1] = {};  // ev_dh[l]: dH_l (and its transposed copy) is ready
+  hipEvent_t ev_wgrad = nullptr;                // all weight gradients of the last worker step are written
+  bool wgrad_pending = false;
   bool presorted = false;
 };
 
@@ -294,6 +298,13 @@ int antdt_destroy(antdt_ctx* ctx) {
     (void)hipEventDestroy(ctx->ev_fork);
     (void)hipEventDestroy(ctx->ev_join);
   }
+  if (ctx->wside) {
+    (void)hipStreamSynchronize(ctx->wside);
+    (void)hipStreamDestroy(ctx->wside);
+    (void)hipEventDestroy(ctx->ev_wgrad);
+    for (auto& e : ctx->ev_dh)
+      if (e) (void)hipEventDestroy(e);
+  }
   for (auto& e : ctx->prof.pool) {
     (void)hipEventDestroy(e.first);
     (void)hipEventDestroy(e.second);
@@ -366,6 +377,11 @@ int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params
     HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
+  }
+  if (!c->wside) {
+    HIP_TRY(c, hipStreamCreateWithFlags(&c->wside, hipStreamNonBlocking));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_wgrad, hipEventDisableTiming));
+    for (int l = 0; l <= c->L; ++l) HIP_TRY(c, hipEventCreateWithFlags(&c->ev_dh[l], hipEventDisableTiming));
   }
   c->stage = ST_BOUND;
   return refresh_bf16_weights(c, (hipStream_t)stream);
@@ -537,6 +553,16 @@ static int build_coalescing(antdt_ctx* c, const int32_t* ids, const int32_t* pay
   return ANTDT_OK;
 }
 
+// Makes `s` wait for the weight-gradient products of the last worker step (they run on their
+// own stream): before anything reads the per-shard dense gradients or overwrites their operands.
+static int join_wgrad(antdt_ctx* c, hipStream_t s) {
+  if (c->wgrad_pending) {
+    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_wgrad, 0));
+    c->wgrad_pending = false;
+  }
+  return ANTDT_OK;
+}
+
 // Forward and backward of shards [k0, k1) as one batched sequence of launches.
 static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream_t s) {
   if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_worker_step: call antdt_set_batch first");
@@ -545,6 +571,10 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
   if (c->presorted) {  // an earlier batched step whose aggregate never came: let its side work finish
     HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
     c->presorted = false;
+  }
+  {  // this step overwrites the operands of the previous step's weight-gradient products
+    const int rc = join_wgrad(c, s);
+    if (rc) return rc;
   }
   Profiler* pr = prof_of(c);
   const antdt_model& m = c->m;
@@ -652,10 +682,16 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       HIP_TRY(c, launch_transpose_bf16(t, s));
     }
   }
+  // Backward.  The data-gradient chain dH_{l+1} -> dH_l stays on the launch stream; the weight
+  // gradient of layer l needs dH_{l+1} but nothing needs it before the dense update, so it goes
+  // to its own stream and runs beside the rest of the chain and the sparse reduction.
+  hipStream_t ws = c->wside ? c->wside : s;
+  if (L > 1 && ws != s) HIP_TRY(c, hipEventRecord(c->ev_dh[L - 1], s));
   ProfScope bwd_scope(c->act_bf16 && L > 1 ? pr : nullptr, KID_GEMM_BWD, s);
-  bwd_scope.launches(2 * (L - 1));
+  bwd_scope.launches(L - 1);
   Profiler* pr_each = c->act_bf16 ? nullptr : pr;  // the fp32 path has other kernels in between
   for (int l = L - 2; l >= 0; --l) {
+    if (ws != s) HIP_TRY(c, hipStreamWaitEvent(ws, c->ev_dh[l + 1], 0));
     if (c->act_bf16) {
       // [dW_l ; db_l][k] = [act_l ; 1]^T dh_{l+1} over the shard's samples: both operands are the
       // transposed copies (sample index contiguous); the ones row yields the bias gradient,
@@ -668,7 +704,8 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       g.M = c->width[l] + 1; g.N = c->width[l + 1]; g.K = 0;
       g.epi = EPI_PLAIN; g.bf16_in = 1; g.bf16_out = 0;
       g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
-      HIP_TRY(c, launch_gemm(g, tab, s));
+      ProfScope ps(pr, KID_GEMM_WGRAD, ws);
+      HIP_TRY(c, launch_gemm(g, tab, ws));
     } else {
       {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
         GemmArgs g;
@@ -679,8 +716,8 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
         g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
         g.epi = EPI_PLAIN; g.bf16_in = 0; g.bf16_out = 0;
         g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
-        ProfScope ps(pr, KID_GEMM_WGRAD, s);
-        HIP_TRY(c, launch_gemm(g, tab, s));
+        ProfScope ps(pr, KID_GEMM_WGRAD, ws);
+        HIP_TRY(c, launch_gemm(g, tab, ws));
       }
       BiasGradArgs b;
       memset(&b, 0, sizeof(b));
@@ -710,8 +747,13 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       ProfScope ps(pr_each, KID_GEMM_DGRAD, s);
       HIP_TRY(c, launch_gemm(g, tab, s));
     }
+    if (l > 0 && ws != s) HIP_TRY(c, hipEventRecord(c->ev_dh[l], s));
   }
   bwd_scope.close();
+  if (L > 1 && ws != s) {
+    HIP_TRY(c, hipEventRecord(c->ev_wgrad, ws));
+    c->wgrad_pending = true;
+  }
   for (int k = k0; k < k1; ++k) c->stepped[k] = true;
   if (c->stage == ST_AGGREGATED) c->stage = ST_BATCH;
   return ANTDT_OK;
@@ -796,6 +838,14 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   Profiler* pr = prof_of(c);
   const antdt_model& m = c->m;
+  // The dense update touches nothing the sparse update touches, so it runs on the
+  // weight-gradient stream (behind those products, which it needs anyway) beside the sparse
+  // update; `s` joins it before this call's work on `s` is complete.
+  hipStream_t ds = c->wside ? c->wside : s;
+  if (ds != s) {
+    HIP_TRY(c, hipEventRecord(c->ev_dh[c->L], s));  // everything enqueued on `s` so far (loss, last layer's gradient)
+    HIP_TRY(c, hipStreamWaitEvent(ds, c->ev_dh[c->L], 0));
+  }
   {  // weighted run sums with the Adagrad step of every touched row applied on the spot
     SegArgs a;
     fill_seg_args(c, a);
@@ -831,8 +881,15 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
     }
     a.n_rng = nr;
     a.rng_block[nr] = rblocks;
-    ProfScope ps(pr, KID_DENSE_ADAGRAD, s);
-    HIP_TRY(c, launch_dense_adagrad(a, c->tab, s));
+    {
+      ProfScope ps(pr, KID_DENSE_ADAGRAD, ds);
+      HIP_TRY(c, launch_dense_adagrad(a, c->tab, ds));
+    }
+    if (ds != s) {
+      HIP_TRY(c, hipEventRecord(c->ev_wgrad, ds));
+      HIP_TRY(c, hipStreamWaitEvent(s, c->ev_wgrad, 0));
+      c->wgrad_pending = false;  // `s` now waits for everything on that stream
+    }
   }
   c->stage = ST_BATCH;
   memset(c->stepped, 0, sizeof(c->stepped));
@@ -887,6 +944,10 @@ int antdt_view_shard_grads(antdt_ctx* c, int32_t k, const float** dense, const f
   if (!c || !dense || !dx || !ld_dx) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: null argument");
   if (!c->have_shards || k < 0 || k >= c->tab.K) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: shard index out of range");
   if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_shard_grads: nothing computed yet");
+  if (c->wgrad_pending) {  // the weight gradients are written on their own stream: wait for it here
+    HIP_TRY(c, hipStreamSynchronize(c->wside));
+    c->wgrad_pending = false;
+  }
   *dense = c->shard_grads + (int64_t)k * c->Pstride;
   *dx = c->dx + (int64_t)c->tab.start[k] * c->FD;
   *ld_dx = c->FD;
@@ -896,6 +957,10 @@ int antdt_view_shard_grads(antdt_ctx* c, int32_t k, const float** dense, const f
 int antdt_view_dense_grad(antdt_ctx* c, const float** g, void* stream) {
   if (!c || !g) return fail(c, ANTDT_INVALID_ARG, "antdt_view_dense_grad: null argument");
   if (c->stage != ST_AGGREGATED) return fail(c, ANTDT_BAD_STATE, "antdt_view_dense_grad: valid between antdt_aggregate and antdt_apply_update");
+  {
+    const int rcj = join_wgrad(c, (hipStream_t)stream);
+    if (rcj) return rcj;
+  }
   if (!c->gdense_valid) {  // written out on request only; apply_update forms the same sum on the fly
     DenseAggArgs d;
     d.grads = c->shard_grads; d.g = c->g_dense; d.P = c->P; d.stride = c->Pstride;

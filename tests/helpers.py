@@ -81,3 +81,20 @@ TINY = wl.RankingConfig("tiny", 2, 7, 3, "f32", "elementwise", 2, (8, 4, 1), "f3
                         (2, 3), wl.SEED0 + 101, min_bag=0)
 SMALL = wl.RankingConfig("small", 3, 50, 4, "f32", "elementwise", 3, (15, 8, 6, 1), "f32", 4, 1.05,
                          (5, 1, 0, 6), wl.SEED0 + 102, min_bag=0)
+
+
+def assert_step_within_bound(step_gpu, step_ref, g_ref, cfg, tol, what):
+    """End-to-end bound on an Adagrad step.  step = lr*g/(sqrt(S+g^2)+eps) has
+    |d step / d g| <= lr/(|g|+eps), so a gradient that is within delta = tol*max|g| of the
+    oracle's moves the step by at most lr*delta/(|g|-delta+eps) (large only where |g| ~ eps),
+    on top of the tolerance on the step itself."""
+    g = np.abs(np.asarray(g_ref, dtype=np.float64))
+    delta = tol * (g.max() if g.size else 0.0)
+    bound = cfg.lr * delta / (np.maximum(g - delta, 0.0) + cfg.eps) + tol * cfg.lr
+    err = np.abs(np.asarray(step_gpu, np.float64) - np.asarray(step_ref, np.float64))
+    worst = float((err / bound).max()) if err.size else 0.0
+    assert worst <= 1.0, f"{what}: step error is {worst:.2f}x the bound"
+    # and the bulk agrees tightly: all but the |g| ~ eps elements
+    big = g > 1e3 * max(delta, cfg.eps)
+    if big.any():
+        assert rel_err(np.asarray(step_gpu)[big], np.asarray(step_ref)[big])[0] <= 10 * tol, what

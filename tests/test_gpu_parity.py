@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import workload as wl
-from helpers import (BF16_MAX_TOL, SMALL, assert_close, flat_dense_grad, flat_layers, oracle_iteration, per_field, rel_err)
+from helpers import (BF16_MAX_TOL, SMALL, assert_close, assert_step_within_bound, flat_dense_grad, flat_layers, oracle_iteration, per_field, rel_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -38,23 +38,6 @@ def make_inputs(cfg, nonzero_state=False, batch_index=0):
         state = np.zeros(shape, np.float32)
         fstate = np.zeros_like(flat)
     return tables, state, flat, fstate, batch
-
-
-def assert_step_within_bound(step_gpu, step_ref, g_ref, cfg, tol, what):
-    """End-to-end bound on an Adagrad step.  step = lr*g/(sqrt(S+g^2)+eps) has
-    |d step / d g| <= lr/(|g|+eps), so a gradient that is within delta = tol*max|g| of the
-    oracle's moves the step by at most lr*delta/(|g|-delta+eps) (large only where |g| ~ eps),
-    on top of the tolerance on the step itself."""
-    g = np.abs(np.asarray(g_ref, dtype=np.float64))
-    delta = tol * (g.max() if g.size else 0.0)
-    bound = cfg.lr * delta / (np.maximum(g - delta, 0.0) + cfg.eps) + tol * cfg.lr
-    err = np.abs(np.asarray(step_gpu, np.float64) - np.asarray(step_ref, np.float64))
-    worst = float((err / bound).max()) if err.size else 0.0
-    assert worst <= 1.0, f"{what}: step error is {worst:.2f}x the bound"
-    # and the bulk agrees tightly: all but the |g| ~ eps elements
-    big = g > 1e3 * max(delta, cfg.eps)
-    if big.any():
-        assert rel_err(np.asarray(step_gpu)[big], np.asarray(step_ref)[big])[0] <= 10 * tol, what
 
 
 def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, fwd_tol=None,
