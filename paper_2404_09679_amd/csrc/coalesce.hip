@@ -12,8 +12,8 @@ namespace {
 
 constexpr int SORT_THREADS = 512;
 constexpr int SORT_WAVES = SORT_THREADS / 64;
-constexpr int SORT_ITEMS = 8;
-constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;  // keys per block
+constexpr int SORT_TILE = ANTDT_SORT_TILE;            // keys per block
+constexpr int SORT_ITEMS = SORT_TILE / SORT_THREADS;
 constexpr int MAX_BINS = 1024;
 
 __device__ __forceinline__ uint64_t lanemask_lt() {
@@ -94,8 +94,8 @@ __global__ __launch_bounds__(MAX_BINS) void sort_scan_kernel(uint32_t* hist, uin
   if (d < nb) digit_base[((int64_t)f << rb) + d] = wbase + incl - run;
 }
 
-// Stable scatter of one tile.  Wave w owns the contiguous 512-key slice w of the tile and
-// walks it in 8 rounds of 64 keys; lanes holding equal digits find each other with one
+// Stable scatter of one tile.  Wave w owns the contiguous slice w of the tile and walks it in
+// rounds of 64 keys; lanes holding equal digits find each other with one
 // ballot per digit bit, the per-wave running count of the digit lives in LDS.
 __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     const int32_t* keys_in, const int32_t* pay_in, int32_t* keys_out, int32_t* pay_out, const uint32_t* hist,

@@ -204,6 +204,9 @@ struct BiasGradArgs {   // db[k][o] = sum over the shard's samples of dh[s, o]
 hipError_t launch_bias_grad(const BiasGradArgs& a, const ShardTab& tab, hipStream_t s);
 
 // ------------------------------------------------------------- coalesce.hip
+// Keys per sort tile (one block of 512 threads, ANTDT_SORT_TILE / 512 keys per thread).
+constexpr int ANTDT_SORT_TILE = 2048;
+
 struct SortPlan {
   int32_t F, B;
   int32_t passes, radix_bits;      // digit width per pass

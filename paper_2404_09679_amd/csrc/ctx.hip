@@ -280,7 +280,7 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
   while ((1ll << bits) < m.rows_per_field) ++bits;
   c->sort_passes = (bits + 9) / 10;
   c->radix_bits = (bits + c->sort_passes - 1) / c->sort_passes;
-  c->max_tiles_total = m.max_nnz / 4096 + m.num_fields + 1;
+  c->max_tiles_total = m.max_nnz / ANTDT_SORT_TILE + m.num_fields + 1;
   c->long_cap = m.max_nnz / c->long_threshold + 1;
   c->item_cap = m.max_nnz / c->chunk + c->long_cap + 1;
   c->ws_bytes = carve(c, nullptr);
@@ -387,12 +387,12 @@ int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params
   return refresh_bf16_weights(c, (hipStream_t)stream);
 }
 
-// Tile decomposition of per-field lookup ranges (4096 keys per tile).
+// Tile decomposition of per-field lookup ranges.
 static void plan_tiles(int F, const FieldPtr& fp, TileBase& tb, int& max_tiles, int& total_tiles) {
   memset(&tb, 0, sizeof(tb));
   max_tiles = 0;
   for (int f = 0; f < F; ++f) {
-    const int tiles = (int)((fp.p[f + 1] - fp.p[f] + 4095) / 4096);
+    const int tiles = (int)((fp.p[f + 1] - fp.p[f] + ANTDT_SORT_TILE - 1) / ANTDT_SORT_TILE);
     tb.t[f + 1] = tb.t[f] + tiles;
     if (tiles > max_tiles) max_tiles = tiles;
   }
