@@ -148,6 +148,10 @@ int antdt_assign_shard(antdt_ctx* ctx, int64_t B, int32_t K, const int64_t* size
  * the shard, flat layout) and d loss_k / d pooled-embedding for each of its samples — the
  * pair (ids, that gradient) is the shard's sparse gradient.  loss_out: DEVICE fp32 [1], may
  * be NULL.  Requires set_batch and assign_shard with matching B.
+ * Everything is enqueued on `stream` except the weight gradients of the hidden layers, which the
+ * library computes on a stream of its own beside the rest of the backward pass: they are
+ * complete, in the order of `stream`, after antdt_apply_update; antdt_view_shard_grads waits
+ * for them on the host.
  */
 int antdt_worker_step(antdt_ctx* ctx, int32_t k, float* loss_out, void* stream);
 

@@ -9,7 +9,8 @@ The counters are in KiB per dispatch.  They are scaled by what the same counter 
 plain copy kernel (1 GiB read and 1 GiB written per launch): on this machine FETCH_SIZE reads
 half the bytes actually fetched.  Dispatches are walked in order; a step starts at the pooling
 kernel, matrix products before the loss kernel are the forward pass, those after it the
-backward pass.  The first five steps are dropped.
+data-gradient chain (gemm_bwd) and the per-shard weight gradients (gemm_wgrad).  The first five
+steps are dropped.
 """
 import collections
 import csv
@@ -39,8 +40,8 @@ def class_totals(rows):
             after_head, cls = True, "head"
         elif "head_reduce" in k:
             cls = "head_reduce"
-        elif "gemm_" in k:
-            cls = "gemm_bwd" if after_head else "gemm_fwd"
+        elif "gemm_" in k:  # the grouped instantiations (last template argument true) are the weight gradients
+            cls = "gemm_fwd" if not after_head else ("gemm_wgrad" if "true>" in k else "gemm_bwd")
         elif "seg_reduce" in k:
             cls = "sparse_adagrad"
         elif "seg_chunk" in k or "seg_finish" in k:
