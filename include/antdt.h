@@ -72,7 +72,7 @@ typedef struct antdt_ctx antdt_ctx; /* opaque; holds host metadata only */
 typedef struct antdt_model {
   int32_t num_fields;       /* F, 1..ANTDT_MAX_FIELDS */
   int64_t rows_per_field;   /* R, < 2^31 */
-  int32_t dim;              /* D; D*sizeof(element) a power-of-two multiple of 16 bytes, <= 1024 B */
+  int32_t dim;              /* D: a power of two, 4..256, with D*sizeof(element) >= 16 bytes */
   int32_t table_dtype;      /* ANTDT_F32 or ANTDT_BF16: element type of the embedding tables */
   int32_t adagrad_state;    /* ELEMENTWISE: fp32 [F*R, D];  ROWWISE: fp32 [F*R] */
   int32_t num_dense;        /* dense features per sample (may be 0) */

@@ -243,7 +243,8 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
   if (m.gemm_dtype != ANTDT_F32 && m.gemm_dtype != ANTDT_BF16) return bad("gemm_dtype");
   if (m.adagrad_state != ANTDT_STATE_ELEMENTWISE && m.adagrad_state != ANTDT_STATE_ROWWISE) return bad("adagrad_state");
   const int64_t row_bytes = (int64_t)m.dim * (m.table_dtype == ANTDT_BF16 ? 2 : 4);
-  if (m.dim < 4 || row_bytes < 16 || row_bytes > 1024 || !is_pow2(row_bytes)) return bad("dim: row must be 16..1024 bytes, a power of two");
+  if (m.dim < 4 || m.dim > 256 || row_bytes < 16 || !is_pow2(row_bytes))
+    return bad("dim: 4..256, a power of two (a row's gradient is summed by at most one wavefront, four columns per lane)");
   if (m.num_dense < 0) return bad("num_dense");
   if (m.num_layers < 1 || m.num_layers > ANTDT_MAX_LAYERS) return bad("num_layers out of range");
   if ((int64_t)m.layer_sizes[0] != (int64_t)m.num_fields * m.dim + m.num_dense) return bad("layer_sizes[0] != num_fields*dim + num_dense");

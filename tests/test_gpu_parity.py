@@ -20,6 +20,16 @@ MID = wl.RankingConfig("mid-f32", 5, 100_000, 32, "f32", "elementwise", 13, (173
 MID_BF = wl.scaled(MID, name="mid-bf16gemm", gemm_dtype="bf16")
 ROW_BF = wl.RankingConfig("rowwise-bf16-tables", 4, 50_000, 64, "bf16", "rowwise", 0, (256, 128, 64, 1), "bf16",
                           50, 1.2, (128, 200, 184), wl.SEED0 + 202)
+# row sizes at the other end of the supported range: 256-byte rows (16 lanes per row in the tile
+# kernel), 512-byte and 1024-byte rows (wavefront-per-bag kernel; up to 64 lanes per run)
+WIDE = [wl.RankingConfig("rows-256B", 3, 3000, 64, "f32", "elementwise", 5, (197, 32, 1), "f32", 80, 1.2,
+                         (70, 58), wl.SEED0 + 204, min_bag=0),
+        wl.RankingConfig("rows-512B", 2, 2000, 128, "f32", "elementwise", 0, (256, 16, 1), "f32", 70, 1.3,
+                         (33, 47), wl.SEED0 + 205),
+        wl.RankingConfig("rows-1024B", 2, 1500, 256, "f32", "rowwise", 3, (515, 24, 1), "f32", 90, 1.2,
+                         (41, 23), wl.SEED0 + 206),
+        wl.RankingConfig("rows-512B-bf16", 2, 1500, 256, "bf16", "rowwise", 0, (512, 16, 1), "f32", 60, 1.2,
+                         (29, 35), wl.SEED0 + 207)]
 ONE_LAYER = wl.RankingConfig("single-layer", 3, 1000, 8, "f32", "elementwise", 2, (26, 1), "f32", 5, 1.05,
                              (40, 24), wl.SEED0 + 203, min_bag=0)
 
@@ -254,6 +264,11 @@ def test_learning_rate_change_between_iterations():
         assert rel_err(new_tables[f * R + u] - tables[f * R + u], upd.rows[f] - tables[f * R + u])[0] <= TOL32
     with pytest.raises(Exception):
         run.ctx.set_lr(float("nan"))
+
+
+@pytest.mark.parametrize("cfg", WIDE, ids=[c.name for c in WIDE])
+def test_wide_rows(cfg):
+    check_iteration(cfg, cfg.shard_sizes, nonzero_state=True, batched=True)
 
 
 def test_single_layer_model():

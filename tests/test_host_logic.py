@@ -37,7 +37,7 @@ def good_model():
 
 
 @pytest.mark.parametrize("field,value", [("num_fields", 0), ("num_fields", 129), ("rows_per_field", 0),
-                                         ("dim", 6), ("dim", 3), ("table_dtype", 2), ("num_layers", 0),
+                                         ("dim", 6), ("dim", 3), ("dim", 512), ("table_dtype", 2), ("num_layers", 0),
                                          ("num_layers", 9), ("max_shards", 65), ("max_batch", 0), ("eps", 0.0),
                                          ("num_dense", 12)])
 def test_create_rejects_bad_models(field, value):
