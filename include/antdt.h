@@ -129,6 +129,15 @@ int antdt_set_batch(antdt_ctx* ctx, const int32_t* ids, const int64_t* field_ptr
                     int64_t B, void* stream);
 
 /*
+ * Optional check of the batch given to antdt_set_batch (the other calls trust it: ids are
+ * clamped into the table, offsets are followed as they are).  Launches a check kernel on
+ * `stream` and waits for it.  ANTDT_INVALID_ARG, naming the lowest offending field, when an id
+ * lies outside [0, rows_per_field) or a field's offsets do not start at 0, decrease, or do not
+ * end at the field's lookup count.
+ */
+int antdt_validate_batch(antdt_ctx* ctx, void* stream);
+
+/*
  * Split the global batch into K contiguous shards (start, length), worker order, lengths
  * summing to B (Section V-C.1; constraint of Eq. 1).  HOST work only.
  *   sizes != NULL : explicit B_k (>= 0, must sum to B);

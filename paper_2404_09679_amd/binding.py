@@ -21,7 +21,7 @@ EXPORTS = [
     "antdt_aggregate", "antdt_apply_update", "antdt_dense_aggregate_adam", "antdt_fill_tables",
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
-    "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr",
+    "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr", "antdt_validate_batch",
 ]
 
 
@@ -74,6 +74,7 @@ def _load():
     lib.antdt_kernel_name.argtypes = [i32]
     lib.antdt_kernel_name.restype = C.c_char_p
     lib.antdt_set_lr.argtypes = [vp, f32]
+    lib.antdt_validate_batch.argtypes = [vp, vp]
     lib.antdt_plan_accumulation.argtypes = [i64, i32, C.POINTER(i32), C.POINTER(C.c_double), C.POINTER(i64),
                                             C.POINTER(i64), i32, i32, C.POINTER(i64), C.POINTER(i32),
                                             C.POINTER(C.c_double)]
@@ -175,6 +176,10 @@ class Context:
                                         B, _stream()))
         self.B = B
         self.field_ptr = [int(v) for v in field_ptr]
+
+    def validate_batch(self):
+        """Raises AntdtError(INVALID_ARG) when the batch has out-of-range ids or malformed offsets."""
+        self._check(lib.antdt_validate_batch(self._h, _stream()))
 
     def assign_shard(self, B: int, K: int, sizes: Optional[Sequence[int]] = None,
                      speed: Optional[Sequence[float]] = None) -> List[Tuple[int, int]]:

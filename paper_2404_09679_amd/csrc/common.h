@@ -110,6 +110,8 @@ struct PoolArgs {
   int32_t table_bf16, x_bf16;
 };
 hipError_t launch_pool(const PoolArgs& a, const FieldPtr& fp, hipStream_t s);
+hipError_t launch_validate(const int32_t* ids, const int32_t* offsets, const FieldPtr& fp, int64_t B, int64_t R, int F,
+                           int32_t* flags, hipStream_t s);
 hipError_t launch_fill_tables(void* tables, int bf16, int F, int64_t R, int D, float scale,
                               hipStream_t s);
 

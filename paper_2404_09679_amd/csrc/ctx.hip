@@ -134,6 +134,7 @@ struct antdt_ctx {
   TileBase atb;
   int amax_tiles = 0, atotal_tiles = 0;
   int64_t* cbase = nullptr;
+  int32_t* vflags = nullptr;  // result of antdt_validate_batch
   // shards
   ShardTab tab;
   bool have_shards = false;
@@ -220,6 +221,7 @@ static size_t carve(antdt_ctx* c, char* base) {
   c->segabs = (int32_t*)take((size_t)(N + 1) * 4);
   c->counters = (int32_t*)take(8);
   c->cbase = (int64_t*)take((size_t)(ANTDT_MAX_FIELDS + 1) * 8);
+  c->vflags = (int32_t*)take(8);
   c->long_seg = (int32_t*)take((size_t)c->long_cap * 12);
   c->items = (int32_t*)take((size_t)c->item_cap * 8);
   c->partial = (float*)take((size_t)c->item_cap * m.dim * 4);
@@ -436,6 +438,21 @@ int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, 
   c->presorted = false;
   memset(c->stepped, 0, sizeof(c->stepped));
   return ANTDT_OK;
+}
+
+int antdt_validate_batch(antdt_ctx* c, void* stream) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_validate_batch: null context");
+  if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_validate_batch: call antdt_set_batch first");
+  hipStream_t s = (hipStream_t)stream;
+  HIP_TRY(c, launch_validate(c->ids, c->offsets, c->fp, c->B, c->m.rows_per_field, c->m.num_fields, c->vflags, s));
+  int32_t fl[2] = {0, 0};
+  HIP_TRY(c, hipMemcpyAsync(fl, c->vflags, sizeof(fl), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  if (fl[0] == 0) return ANTDT_OK;
+  std::string what = "antdt_validate_batch: field " + std::to_string(fl[1] - 1) + " (lowest offending):";
+  if (fl[0] & 1) what += " an id outside [0, rows_per_field)";
+  if (fl[0] & 2) what += std::string(fl[0] & 1 ? ";" : "") + " offsets that do not start at 0, decrease, or do not end at the field's lookup count";
+  return fail(c, ANTDT_INVALID_ARG, what);
 }
 
 int antdt_assign_shard(antdt_ctx* c, int64_t B, int32_t K, const int64_t* sizes, const double* speed,

@@ -1,5 +1,7 @@
 // Embedding-bag gather and sum-pool (worker side of the iteration, Section II:
 // the forward pass on the local batch B_k), plus the procedural table fill.
+#include <algorithm>
+
 #include "common.h"
 
 namespace antdt {
@@ -198,6 +200,48 @@ static void launch_pool_typed(const PoolArgs& a, const FieldPtr& fp, hipStream_t
     hipLaunchKernelGGL((pool_kernel<TT, OT>), dim3((unsigned)((items + 3) / 4)), block, 0, s, a, fp);
     hipLaunchKernelGGL((pool_dense_kernel<OT>), dim3((a.ns + 63) / 64), block, 0, s, a);
   }
+}
+
+// Input check: flags[0] bit 0 = an id outside [0, R), bit 1 = offsets of a field that do not
+// start at 0, decrease, or do not end at the field's lookup count; flags[1] = lowest offending
+// field + 1.  Reads only what the host-side sizes cover, never through an offset.
+__global__ __launch_bounds__(256) void validate_kernel(const int32_t* ids, const int32_t* offsets, FieldPtr fp,
+                                                       int64_t B, int64_t R, int F, int32_t* flags) {
+  const int f = blockIdx.y;
+  const int64_t n = fp.p[f + 1] - fp.p[f];
+  const int32_t* off = offsets + (int64_t)f * (B + 1);
+  int bad = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int32_t id = ids[fp.p[f] + i];
+    if (id < 0 || id >= R) bad |= 1;
+  }
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i <= B; i += (int64_t)gridDim.x * 256) {
+    const int64_t v = off[i];
+    if (i == 0 && v != 0) bad |= 2;
+    if (i == B && v != n) bad |= 2;
+    if (i > 0 && v < off[i - 1]) bad |= 2;
+  }
+  if (bad) {
+    atomicOr(&flags[0], bad);
+    atomicMin(&flags[1], f + 1);
+  }
+}
+
+__global__ void validate_reset_kernel(int32_t* flags) {
+  if (threadIdx.x == 0) {
+    flags[0] = 0;
+    flags[1] = 0x7FFFFFFF;
+  }
+}
+
+hipError_t launch_validate(const int32_t* ids, const int32_t* offsets, const FieldPtr& fp, int64_t B, int64_t R, int F,
+                           int32_t* flags, hipStream_t s) {
+  hipLaunchKernelGGL(validate_reset_kernel, dim3(1), dim3(64), 0, s, flags);
+  int64_t work = B + 1;
+  for (int f = 0; f < F; ++f) work = std::max<int64_t>(work, fp.p[f + 1] - fp.p[f]);
+  const unsigned bx = (unsigned)std::min<int64_t>((work + 255) / 256, 1024);
+  hipLaunchKernelGGL(validate_kernel, dim3(bx, F), dim3(256), 0, s, ids, offsets, fp, B, R, F, flags);
+  return hipGetLastError();
 }
 
 hipError_t launch_pool(const PoolArgs& a, const FieldPtr& fp, hipStream_t s) {

@@ -271,6 +271,43 @@ def test_wide_rows(cfg):
     check_iteration(cfg, cfg.shard_sizes, nonzero_state=True, batched=True)
 
 
+def test_validate_batch_reports_bad_ids_and_offsets():
+    """The optional input check: a good batch passes; an id outside the table, offsets that do
+    not start at 0, decrease, or end short of the field's lookups are reported with the field."""
+    import paper_2404_09679_amd as A
+    from gpu_helpers import GpuRun
+    cfg = wl.CONFIGS[1]
+    tables, state, flat, fstate, batch = make_inputs(cfg)
+    run = GpuRun(cfg, tables, flat, state, fstate, max_batch=batch.batch, max_shards=len(cfg.shard_sizes))
+    run.set_batch(batch)
+    run.ctx.validate_batch()
+
+    def expect_error(ids, offsets, field, word):
+        b = wl.Batch(ids, batch.field_ptr, offsets, batch.dense, batch.labels)
+        run.set_batch(b)
+        with pytest.raises(A.AntdtError) as e:
+            run.ctx.validate_batch()
+        assert e.value.code == -1 and f"field {field}" in str(e.value) and word in str(e.value)
+
+    ids = batch.ids.copy()
+    ids[batch.field_ptr[3] + 5] = cfg.rows_per_field          # one past the last row, field 3
+    expect_error(ids, batch.offsets, 3, "id outside")
+    ids = batch.ids.copy()
+    ids[batch.field_ptr[6]] = -1
+    expect_error(ids, batch.offsets, 6, "id outside")
+    off = batch.offsets.copy()
+    off[2, 10], off[2, 11] = off[2, 11], off[2, 10] - 1       # decreasing
+    expect_error(batch.ids, off, 2, "offsets")
+    off = batch.offsets.copy()
+    off[5, -1] -= 1                                           # ends short of the field's lookups
+    expect_error(batch.ids, off, 5, "offsets")
+    off = batch.offsets.copy()
+    off[0, 0] = 1
+    expect_error(batch.ids, off, 0, "offsets")
+    run.set_batch(batch)
+    run.ctx.validate_batch()
+
+
 def test_single_layer_model():
     check_iteration(ONE_LAYER, ONE_LAYER.shard_sizes)
 
