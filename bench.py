@@ -311,6 +311,50 @@ def run_batch_sweep(args):
             "samples_per_s": [[bk, bk / (us * 1e-6)] for bk, us in curve]}
 
 
+def run_straggler_sim(args):
+    """Job completion times under the injection pattern of Section VII-A.2, from the batch times
+    measured on this GPU: ten workers whose batch time is the affine fit of the measured
+    F(B_k) curve, the server term the measured aggregate + update time of a whole batch, and
+    every duration of the pattern (sleep 1.5 s, bursts of 15 in 30 minutes, decisions every
+    5 minutes, windows of 5 and 10 minutes, restart 2 minutes) scaled by (measured batch time
+    of B/n samples) / 0.5 s, so that delays and batch times keep the proportions of the
+    evaluation's CPU workers.  The host-side model is antdt_simulate_bsp."""
+    import numpy as np
+
+    import paper_2404_09679_amd as A
+
+    sweep = run_batch_sweep(args)
+    bk = np.array([p[0] for p in sweep["curve_us"]], float)
+    us = np.array([p[1] for p in sweep["curve_us"]], float)
+    slope, icpt = np.polyfit(bk, us, 1)                      # F(b) = icpt + slope * b, microseconds
+    n, B = 10, 4096
+    t0, v = max(icpt, 0.0) * 1e-6, 1.0 / (slope * 1e-6)
+    base = t0 + (B / n) / v
+    scale = base / 0.5
+    common = dict(n=n, B=B, N=B * 20000, t0=[t0] * n, v=[v] * n, t_server=0.2 * base, period=1800.0 * scale,
+                  duration=900.0 * scale, sleep_duration=1.5 * scale, decide_every=300.0 * scale,
+                  L_trans=300.0 * scale, L_per=600.0 * scale, lam=1.5, restart_cost=120.0 * scale, seed=20240413)
+    names = ["BSP", "ADJUST_BS", "BACKUP_WORKERS(b=3)", "AntDT-ND"]
+    rows = []
+    for intensity in (0.1, 0.2, 0.4, 0.8):
+        jct = [A.simulate_bsp(policy=p, backup_b=3 if p == 2 else 0, prob=0.3, intensity=intensity, **common)[0].jct
+               for p in range(4)]
+        rows.append({"pattern": f"transient, intensity {intensity}", **{nm: j / jct[0] for nm, j in zip(names, jct)},
+                     "BSP_seconds": jct[0]})
+    pers = [0.0] * n
+    pers[3] = 4.0 * scale
+    jct = [A.simulate_bsp(policy=p, backup_b=3 if p == 2 else 0, prob=0.0, persistent_delay=pers, **common)[0].jct
+           for p in range(4)]
+    rows.append({"pattern": "one persistent straggler (4 s)", **{nm: j / jct[0] for nm, j in zip(names, jct)},
+                 "BSP_seconds": jct[0]})
+    return {"metric": "job completion time relative to BSP (host-side model on measured batch times)",
+            "unit": "ratio", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False,
+            "data": "synthetic", "dtype": "f64",
+            "config": {"workload": "configs[1] batch times, 10 simulated workers, global batch 4096, 20000 iterations",
+                       "batch_time_fit_us": {"floor": icpt, "per_sample": slope}, "time_scale": scale},
+            "table": rows}
+
+
 def run_copy_calibration(args):
     """A plain elementwise copy of known size (1 GiB read, 1 GiB written per launch): the
     reference against which the HBM byte counters of a profiler run are scaled."""
@@ -381,13 +425,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "batch-sweep", "copy-calibration"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "batch-sweep", "copy-calibration", "straggler-sim"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the K workers are shards on that device); "
                  "use --gpus 1")
-    if args.workload == "copy-calibration":
+    if args.workload == "straggler-sim":
+        out = run_straggler_sim(args)
+    elif args.workload == "copy-calibration":
         out = run_copy_calibration(args)
     elif args.workload == "batch-sweep":
         out = run_batch_sweep(args)

@@ -48,7 +48,8 @@ enum {
   ANTDT_WORKSPACE_TOO_SMALL = -3,
   ANTDT_HIP_ERROR = -4,           /* a HIP runtime call failed; message holds hipGetErrorString */
   ANTDT_UNSUPPORTED = -5,
-  ANTDT_INFEASIBLE = -6           /* a planning problem has no solution within its bounds */
+  ANTDT_INFEASIBLE = -6,          /* a planning problem has no solution within its bounds */
+  ANTDT_EMPTY = -7                /* the shard queue holds no waiting shard */
 };
 
 enum { ANTDT_F32 = 0, ANTDT_BF16 = 1 };
@@ -229,6 +230,80 @@ int antdt_plan_accumulation(int64_t B, int32_t k, const int32_t* n, const double
 int antdt_expand_accumulation(int32_t k, const int32_t* n, const int64_t* B_i, const int32_t* C_i,
                               int32_t cap, int64_t* sizes_out, int32_t* device_out,
                               int32_t* count_out);
+
+/*
+ * Shard queue with states (Section V-B, the stateful dynamic data sharding service).  The N
+ * samples of a data set are cut into K = ceil(N / (B*M)) shards of M batches, each a pair
+ * (start offset, length); only the last may be short.  All shards start as TODO, in a queue in
+ * index order.  antdt_dds_fetch hands the head of the queue to a worker (TODO -> DOING; EMPTY when
+ * nothing waits).  antdt_dds_report_done marks a shard DONE once its worker has pushed its
+ * gradients (BAD_STATE unless that worker holds the shard as DOING).  antdt_dds_release_worker is
+ * for a worker that is lost (its gradients were disregarded, or its node was killed): its DOING
+ * shards become TODO again and are appended to the END of the queue in index order, which gives
+ * at-least-once processing.  Host only; not thread-safe.
+ */
+typedef struct antdt_dds antdt_dds;
+enum { ANTDT_SHARD_TODO = 0, ANTDT_SHARD_DOING = 1, ANTDT_SHARD_DONE = 2 };
+int antdt_dds_create(int64_t N, int64_t B, int32_t M, antdt_dds** out);
+int antdt_dds_destroy(antdt_dds* dds);
+int antdt_dds_num_shards(const antdt_dds* dds, int64_t* K);
+int antdt_dds_fetch(antdt_dds* dds, int32_t worker, int64_t* shard, int64_t* start, int64_t* len);
+int antdt_dds_report_done(antdt_dds* dds, int64_t shard, int32_t worker);
+int antdt_dds_release_worker(antdt_dds* dds, int32_t worker, int64_t* requeued /* may be NULL */);
+/* start, len, state, owner (worker holding it as DOING, else -1): each may be NULL */
+int antdt_dds_shard(const antdt_dds* dds, int64_t shard, int64_t* start, int64_t* len,
+                    int32_t* state, int32_t* owner);
+int antdt_dds_counts(const antdt_dds* dds, int64_t* todo, int64_t* doing, int64_t* done);
+
+/*
+ * Iteration-level model of bulk-synchronous training under injected stragglers, to turn measured
+ * batch times into job completion times.  One iteration of the present workers takes
+ *   max_i T_i + t_server,   T_i = t0[i] + B_i / v[i] + delay_i,   sum_i B_i = B
+ * (Eq. 1 of Section II with the server and communication terms lumped into t_server; the batch
+ * time F(B_i) is affine: a latency floor t0 plus B_i / v).  Delays (Section VII-A.2): during the
+ * first `duration` seconds of every `period` seconds a disturbed worker adds
+ * sleep_duration * intensity to each of its iterations; the pair (window w, worker i) is
+ * disturbed when fmix32(seed ^ fmix32(w * 0x9E3779B9 + i + 1)) / 2^32 < prob (fmix32:
+ * MurmurHash3's 32-bit finaliser); persistent_delay[i] (may be NULL) is added from the start.
+ * The job ends when N samples are processed.  Policies:
+ *   BSP            equal split (first B mod n workers one more), never changed;
+ *   ADJUST_BS      at the first iteration end at or after every multiple of decide_every: per
+ *                  present worker the mean batch time over the iterations that ended within
+ *                  the last L_trans seconds; if the largest is >= lambda * their mean, or the
+ *                  smallest * lambda <= their mean, the split is re-solved (Eq. 3, the rule of
+ *                  antdt_assign_shard in double precision) from v_i = mean of B_i / T_i over the
+ *                  same window;
+ *   BACKUP_WORKERS the backup_b slowest workers of every iteration (ties: higher index first) are
+ *                  disregarded: the iteration takes the slowest remaining worker's time and only
+ *                  the remaining workers' samples count as processed (Section VII-A.3);
+ *   ANTDT_ND       ADJUST_BS, preceded at each decision by: mean batch times over L_per seconds;
+ *                  if the slowest worker (ties: lowest index) is >= lambda * their mean it is
+ *                  killed: absent for restart_cost seconds, back without its persistent delay
+ *                  and with an empty history; no ADJUST_BS at that decision (Section VI-A).
+ * Whenever the set of present workers changes the batch is split equally among them.
+ * final_sizes: HOST int64 [n] (may be NULL), the split when the job ended.  Host only.
+ */
+enum { ANTDT_POLICY_BSP = 0, ANTDT_POLICY_ADJUST_BS = 1, ANTDT_POLICY_BACKUP_WORKERS = 2, ANTDT_POLICY_ANTDT_ND = 3 };
+typedef struct {
+  int32_t n;                      /* workers, 1..64 */
+  int64_t B, N;                   /* global batch (>= n), samples of the job */
+  const double* t0;               /* HOST [n] seconds */
+  const double* v;                /* HOST [n] samples per second */
+  double t_server;
+  double period, duration, prob, sleep_duration, intensity;
+  uint32_t seed;
+  const double* persistent_delay; /* HOST [n] seconds, or NULL */
+  int32_t policy, backup_b;
+  double decide_every, L_trans, L_per, lambda, restart_cost;
+  int64_t max_iterations;         /* the simulation stops there at the latest */
+} antdt_sim_config;
+typedef struct {
+  double jct;                     /* job completion time, seconds */
+  int64_t iterations, processed;
+  int32_t adjust_actions, kills;
+  double max_bpt, sum_bpt;        /* largest and summed batch processing time (without t_server) */
+} antdt_sim_result;
+int antdt_simulate_bsp(const antdt_sim_config* cfg, antdt_sim_result* result, int64_t* final_sizes);
 
 /*
  * Dense data-parallel step on one device (Section II: the AllReduce variant drops the

@@ -48,3 +48,12 @@ from .shard_assign import (  # noqa: F401
     data_shards,
     accumulation_plan_bruteforce,
 )
+from .dds_sim import (  # noqa: F401
+    ShardQueue,
+    SimConfig,
+    SimResult,
+    simulate_bsp,
+    split_by_speed,
+    equal_sizes,
+    disturbed,
+)

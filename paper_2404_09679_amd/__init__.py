@@ -8,6 +8,8 @@ shared library has not been built (python paper_2404_09679_amd/build.py).
 from .binding import (  # noqa: F401
     AntdtError,
     Context,
+    ShardQueue,
+    simulate_bsp,
     Model,
     dense_aggregate_adam,
     expand_accumulation,

@@ -22,6 +22,8 @@ EXPORTS = [
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
     "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr", "antdt_validate_batch",
+    "antdt_dds_create", "antdt_dds_destroy", "antdt_dds_num_shards", "antdt_dds_fetch", "antdt_dds_report_done",
+    "antdt_dds_release_worker", "antdt_dds_shard", "antdt_dds_counts", "antdt_simulate_bsp",
 ]
 
 
@@ -39,6 +41,21 @@ class Model(C.Structure):
         ("gemm_dtype", C.c_int32), ("lr", C.c_float), ("eps", C.c_float),
         ("max_shards", C.c_int32), ("max_batch", C.c_int64), ("max_nnz", C.c_int64),
     ]
+
+
+class SimConfig(C.Structure):
+    _fields_ = [("n", C.c_int32), ("B", C.c_int64), ("N", C.c_int64), ("t0", C.POINTER(C.c_double)),
+                ("v", C.POINTER(C.c_double)), ("t_server", C.c_double), ("period", C.c_double),
+                ("duration", C.c_double), ("prob", C.c_double), ("sleep_duration", C.c_double),
+                ("intensity", C.c_double), ("seed", C.c_uint32), ("persistent_delay", C.POINTER(C.c_double)),
+                ("policy", C.c_int32), ("backup_b", C.c_int32), ("decide_every", C.c_double),
+                ("L_trans", C.c_double), ("L_per", C.c_double), ("lam", C.c_double), ("restart_cost", C.c_double),
+                ("max_iterations", C.c_int64)]
+
+
+class SimResult(C.Structure):
+    _fields_ = [("jct", C.c_double), ("iterations", C.c_int64), ("processed", C.c_int64),
+                ("adjust_actions", C.c_int32), ("kills", C.c_int32), ("max_bpt", C.c_double), ("sum_bpt", C.c_double)]
 
 
 def _load():
@@ -75,6 +92,15 @@ def _load():
     lib.antdt_kernel_name.restype = C.c_char_p
     lib.antdt_set_lr.argtypes = [vp, f32]
     lib.antdt_validate_batch.argtypes = [vp, vp]
+    lib.antdt_dds_create.argtypes = [i64, i64, i32, C.POINTER(vp)]
+    lib.antdt_dds_destroy.argtypes = [vp]
+    lib.antdt_dds_num_shards.argtypes = [vp, C.POINTER(i64)]
+    lib.antdt_dds_fetch.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.antdt_dds_report_done.argtypes = [vp, i64, i32]
+    lib.antdt_dds_release_worker.argtypes = [vp, i32, C.POINTER(i64)]
+    lib.antdt_dds_shard.argtypes = [vp, i64, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
+    lib.antdt_dds_counts.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.antdt_simulate_bsp.argtypes = [C.POINTER(SimConfig), C.POINTER(SimResult), C.POINTER(i64)]
     lib.antdt_plan_accumulation.argtypes = [i64, i32, C.POINTER(i32), C.POINTER(C.c_double), C.POINTER(i64),
                                             C.POINTER(i64), i32, i32, C.POINTER(i64), C.POINTER(i32),
                                             C.POINTER(C.c_double)]
@@ -307,3 +333,80 @@ def expand_accumulation(counts: Sequence[int], batch_sizes: Sequence[int], accum
     if rc:
         raise AntdtError(rc, lib.antdt_last_error(None).decode())
     return list(sizes)[:cnt.value], list(dev)[:cnt.value]
+
+
+EMPTY = -7
+POLICY_BSP, POLICY_ADJUST_BS, POLICY_BACKUP_WORKERS, POLICY_ANTDT_ND = 0, 1, 2, 3
+
+
+def _raise(rc: int):
+    raise AntdtError(rc, lib.antdt_last_error(None).decode())
+
+
+class ShardQueue:
+    """The shard queue with states of Section V-B (see antdt_dds_* in antdt.h)."""
+
+    def __init__(self, N: int, B: int, M: int):
+        h = C.c_void_p()
+        rc = lib.antdt_dds_create(N, B, M, C.byref(h))
+        if rc:
+            _raise(rc)
+        self._h = h
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib.antdt_dds_destroy(self._h)
+            self._h = None
+
+    def num_shards(self) -> int:
+        k = C.c_int64()
+        lib.antdt_dds_num_shards(self._h, C.byref(k))
+        return k.value
+
+    def fetch(self, worker: int):
+        k, st, ln = C.c_int64(), C.c_int64(), C.c_int64()
+        rc = lib.antdt_dds_fetch(self._h, worker, C.byref(k), C.byref(st), C.byref(ln))
+        if rc == EMPTY:
+            return None
+        if rc:
+            _raise(rc)
+        return k.value, st.value, ln.value
+
+    def report_done(self, shard: int, worker: int):
+        rc = lib.antdt_dds_report_done(self._h, shard, worker)
+        if rc:
+            _raise(rc)
+
+    def release_worker(self, worker: int) -> int:
+        n = C.c_int64()
+        rc = lib.antdt_dds_release_worker(self._h, worker, C.byref(n))
+        if rc:
+            _raise(rc)
+        return n.value
+
+    def shard(self, k: int):
+        st, ln, state, owner = C.c_int64(), C.c_int64(), C.c_int32(), C.c_int32()
+        rc = lib.antdt_dds_shard(self._h, k, C.byref(st), C.byref(ln), C.byref(state), C.byref(owner))
+        if rc:
+            _raise(rc)
+        return st.value, ln.value, state.value, owner.value
+
+    def counts(self):
+        a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+        lib.antdt_dds_counts(self._h, C.byref(a), C.byref(b), C.byref(c))
+        return a.value, b.value, c.value
+
+
+def simulate_bsp(n, B, N, t0, v, t_server=0.0, period=1800.0, duration=900.0, prob=0.0, sleep_duration=1.5,
+                 intensity=0.0, seed=1, persistent_delay=None, policy=POLICY_BSP, backup_b=0, decide_every=300.0,
+                 L_trans=300.0, L_per=600.0, lam=1.5, restart_cost=120.0, max_iterations=10_000_000):
+    """Job completion time model (see antdt_simulate_bsp in antdt.h).  Returns (SimResult, final sizes)."""
+    dbl = C.c_double * n
+    cfg = SimConfig(n, B, N, dbl(*t0), dbl(*v), t_server, period, duration, prob, sleep_duration, intensity, seed,
+                    dbl(*persistent_delay) if persistent_delay is not None else None, policy, backup_b,
+                    decide_every, L_trans, L_per, lam, restart_cost, max_iterations)
+    res, sizes = SimResult(), (C.c_int64 * n)()
+    rc = lib.antdt_simulate_bsp(C.byref(cfg), C.byref(res), sizes)
+    if rc:
+        _raise(rc)
+    return res, list(sizes)

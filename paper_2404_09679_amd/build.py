@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libantdt_hip.so")
-SOURCES = ["ctx.hip", "embed.hip", "gemm.hip", "head.hip", "coalesce.hip", "optim.hip", "plan.hip"]
+SOURCES = ["ctx.hip", "embed.hip", "gemm.hip", "head.hip", "coalesce.hip", "optim.hip", "plan.hip", "sim.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -188,3 +188,100 @@ def test_expand_accumulation_lists_micro_batches_device_by_device():
     assert sizes == [4, 4, 4, 4, 3, 3, 3]
     assert dev == [0, 0, 1, 1, 2, 2, 2]
     assert A.expand_accumulation((1,), (5,), (0,)) == ([], [])
+
+
+# ------------------------------------------------------------------ shard queue (Section V-B)
+def test_shard_queue_matches_the_oracle_step_by_step():
+    rng = np.random.default_rng(17)
+    for N, B, M in [(5003, 7, 13), (100, 10, 10), (1, 4, 100), (0, 3, 2), (999, 1, 1)]:
+        lib_q, ref = A.ShardQueue(N, B, M), oracle.ShardQueue(N, B, M)
+        K = lib_q.num_shards()
+        assert K == len(ref.shards) == oracle.num_data_shards(N, B, M)
+        assert [lib_q.shard(k)[:2] for k in range(K)] == list(ref.shards)
+        for _ in range(6 * K + 20):
+            w, r = int(rng.integers(0, 4)), rng.random()
+            if r < 0.5:
+                assert lib_q.fetch(w) == ref.fetch(w)
+            elif r < 0.85 and K:
+                k = int(rng.integers(0, K))
+                try:
+                    ref.report_done(k, w)
+                    ok = True
+                except ValueError:
+                    ok = False
+                if ok:
+                    lib_q.report_done(k, w)
+                else:
+                    with pytest.raises(A.AntdtError) as e:
+                        lib_q.report_done(k, w)
+                    assert e.value.code == -2
+            else:
+                assert lib_q.release_worker(w) == ref.release_worker(w)
+            assert lib_q.counts() == ref.counts()
+            assert all(lib_q.shard(k)[2:] == (ref.state[k], ref.owner[k]) for k in range(K))
+    with pytest.raises(A.AntdtError):
+        A.ShardQueue(10, 0, 1)
+    with pytest.raises(A.AntdtError):
+        A.ShardQueue(10, 2, 2).report_done(99, 0)
+
+
+# ------------------------------------------------------------------ training model
+def _same_simulation(**kw):
+    ref = oracle.simulate_bsp(oracle.SimConfig(**kw))
+    kw = dict(kw)
+    got, sizes = A.simulate_bsp(**kw)
+    assert (got.iterations, got.processed, got.adjust_actions, got.kills) == \
+        (ref.iterations, ref.processed, ref.adjust_actions, ref.kills)
+    assert sizes == ref.final_sizes
+    # the same operations in the same order on both sides: agreement to the last bits
+    for a, b in ((got.jct, ref.jct), (got.max_bpt, ref.max_bpt), (got.sum_bpt, ref.sum_bpt)):
+        assert abs(a - b) <= 1e-12 * abs(b)
+    return got
+
+
+def test_training_model_matches_the_oracle_for_every_policy():
+    rng = np.random.default_rng(23)
+    for trial in range(24):
+        n = int(rng.integers(2, 11))
+        B = int(rng.integers(n, 40)) * int(rng.integers(1, 60))
+        kw = dict(n=n, B=B, N=B * int(rng.integers(50, 1500)),
+                  t0=[float(x) for x in rng.uniform(0.0, 0.2, n)], v=[float(x) for x in rng.uniform(50.0, 500.0, n)],
+                  t_server=float(rng.uniform(0.0, 0.1)), period=float(rng.choice([200.0, 1800.0])),
+                  duration=float(rng.choice([50.0, 900.0])), prob=float(rng.choice([0.0, 0.3, 0.6])),
+                  sleep_duration=1.5, intensity=float(rng.choice([0.1, 0.4, 0.8])), seed=int(rng.integers(1, 1 << 31)),
+                  persistent_delay=[float(x) for x in (rng.random(n) < 0.2) * 4.0], policy=trial % 4,
+                  backup_b=int(rng.integers(0, max(n // 2, 1))) if trial % 4 == 2 else 0,
+                  decide_every=float(rng.choice([20.0, 300.0])), L_trans=float(rng.choice([20.0, 300.0])),
+                  L_per=float(rng.choice([40.0, 600.0])), lam=float(rng.choice([1.2, 1.5])),
+                  restart_cost=float(rng.choice([0.0, 30.0, 120.0])))
+        _same_simulation(**kw)
+
+
+def test_training_model_with_the_injection_pattern_of_the_evaluation():
+    """Ten workers, disturbed with probability 0.3 for 15 of every 30 minutes, sleep 1.5 s times the
+    intensity; a persistent straggler adds 4 s (Section VII-A.2).  Batch time: the affine fit of
+    a worker that needs 0.45 s for its tenth of the global batch."""
+    kw = dict(n=10, B=4096, N=4096 * 6000, t0=[0.05] * 10, v=[4096 / 10 / 0.40] * 10, t_server=0.05,
+              prob=0.3, sleep_duration=1.5, decide_every=300.0, L_trans=300.0, L_per=600.0, lam=1.5)
+    jct = {}
+    for intensity in (0.1, 0.8):
+        for pol in range(4):
+            r = _same_simulation(policy=pol, intensity=intensity, backup_b=3 if pol == 2 else 0, **kw)
+            jct[intensity, pol] = r.jct
+    assert jct[0.8, 0] > jct[0.1, 0]                            # stronger disturbance, slower synchronous job
+    r = _same_simulation(policy=3, intensity=0.0, prob=0.0, persistent_delay=[0.0] * 9 + [4.0], **{
+        k: v for k, v in kw.items() if k != "prob"})
+    assert r.kills == 1
+
+
+def test_training_model_rejects_bad_arguments():
+    ok = dict(n=2, B=10, N=100, t0=[0.1, 0.1], v=[10.0, 10.0])
+    A.simulate_bsp(**ok)
+    for bad in (dict(n=0), dict(B=1), dict(N=0), dict(v=[10.0, 0.0]), dict(t0=[-1.0, 0.1]), dict(policy=4),
+                dict(backup_b=2, policy=2), dict(lam=0.5), dict(period=0.0), dict(decide_every=0.0)):
+        kw = dict(ok)
+        kw.update(bad)
+        if "n" in bad:
+            kw["t0"], kw["v"] = [], []
+        with pytest.raises(A.AntdtError):
+            A.simulate_bsp(**kw)

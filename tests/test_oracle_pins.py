@@ -435,3 +435,114 @@ def test_eq4_bruteforce():
         assert max(C[0] * Bs[0] / 1.0, C[1] * Bs[1] / 3.0) == float(z)
     assert float(z) == 8.0          # 8 samples on the slow type, 24 on the fast one
     assert oracle.accumulation_plan_bruteforce(5, (2,), (1.0,), (1,), (2,), 1, 1)[0] is None
+
+
+# ------------------------------------------------------------------ shard queue and training model
+def test_shard_queue_states_and_requeue_at_the_tail():
+    """Section V-B: shards (start, length) in index order; fetch TODO -> DOING, report -> DONE,
+    a lost worker's DOING shards go back to TODO at the END of the queue."""
+    q = oracle.ShardQueue(N=1050, B=10, M=10)                 # K = ceil(1050 / 100) = 11, last one short
+    assert q.shards == oracle.data_shards(1050, 10, 10) and len(q.shards) == 11 and q.shards[-1] == (1000, 50)
+    assert q.counts() == (11, 0, 0)
+    a = q.fetch(worker=0)
+    b = q.fetch(worker=1)
+    c = q.fetch(worker=0)
+    assert (a, b, c) == ((0, 0, 100), (1, 100, 100), (2, 200, 100)) and q.counts() == (8, 3, 0)
+    q.report_done(1, worker=1)
+    with pytest.raises(ValueError):
+        q.report_done(1, worker=1)                            # already DONE
+    with pytest.raises(ValueError):
+        q.report_done(0, worker=1)                            # held by another worker
+    assert q.release_worker(0) == 2 and q.counts() == (10, 0, 1)
+    order = []
+    while True:
+        s = q.fetch(worker=2)
+        if s is None:
+            break
+        order.append(s[0])
+        q.report_done(s[0], worker=2)
+    assert order == [3, 4, 5, 6, 7, 8, 9, 10, 0, 2]           # the lost shards come last, ascending
+    assert q.counts() == (0, 0, 11)
+
+
+def test_shard_queue_at_least_once_under_random_losses():
+    rng = np.random.default_rng(3)
+    q = oracle.ShardQueue(N=5003, B=7, M=13)
+    seen = np.zeros(5003, int)
+    holding = {w: [] for w in range(5)}
+    while q.counts()[2] < len(q.shards):
+        w = int(rng.integers(0, 5))
+        r = rng.random()
+        if r < 0.5:
+            s = q.fetch(w)
+            if s is not None:
+                holding[w].append(s)
+        elif r < 0.85 and holding[w]:
+            k, st, ln = holding[w].pop(0)
+            seen[st:st + ln] += 1                              # its gradients were pushed
+            q.report_done(k, w)
+        elif holding[w]:
+            assert q.release_worker(w) == len(holding[w])
+            holding[w] = []
+        t, d, dn = q.counts()
+        assert t + d + dn == len(q.shards) and d == sum(len(h) for h in holding.values())
+    assert np.all(seen == 1)                                   # every sample pushed exactly once here
+
+
+def test_split_by_speed_rule_is_optimal_for_eq3():
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        n = int(rng.integers(1, 4))
+        B = int(rng.integers(n, 14))
+        speeds = [float(x) for x in rng.choice([0.5, 1.0, 1.5, 2.0, 3.0, 0.7], n)]
+        got = oracle.split_by_speed(B, speeds)
+        best, _ = oracle.minmax_split_bruteforce(B, speeds)
+        assert sum(got) == B and oracle.minmax_objective(got, speeds) == best
+    assert oracle.split_by_speed(12, [1.0, 1.0, 1.0]) == [4, 4, 4]
+    assert oracle.equal_sizes(14, 4) == [4, 4, 3, 3]
+
+
+def _sim(**kw):
+    base = dict(n=4, B=400, N=400 * 50, t0=[0.1] * 4, v=[200.0] * 4, t_server=0.05)
+    base.update(kw)
+    return oracle.simulate_bsp(oracle.SimConfig(**base))
+
+
+def test_training_model_closed_forms():
+    from oracle import dds_sim as D
+    # no stragglers: every iteration takes t0 + (B/n)/v + t_server (Eq. 1 with equal workers)
+    r = _sim()
+    assert r.iterations == 50 and r.processed == 400 * 50 and r.final_sizes == [100] * 4
+    assert abs(r.jct - 50 * (0.1 + 100 / 200.0 + 0.05)) < 1e-9
+    # a persistent straggler sets the pace of bulk-synchronous training
+    r = _sim(persistent_delay=[0.0, 4.0, 0.0, 0.0])
+    assert abs(r.jct - 50 * (0.1 + 0.5 + 4.0 + 0.05)) < 1e-9 and abs(r.max_bpt - 4.6) < 1e-12
+    # backup workers: the straggler is disregarded, its 100 samples per iteration go back to the queue
+    r = _sim(persistent_delay=[0.0, 4.0, 0.0, 0.0], policy=D.BACKUP_WORKERS, backup_b=1)
+    assert r.iterations == -(-400 * 50 // 300) and abs(r.jct - r.iterations * 0.65) < 1e-9
+    assert r.processed == r.iterations * 300
+    # heterogeneous speeds without a latency floor: ADJUST_BS reaches the Eq. 3 split of the true speeds
+    v = [100.0, 200.0, 300.0, 400.0]
+    r = _sim(t0=[0.0] * 4, v=v, policy=D.ADJUST_BS, decide_every=20.0, L_trans=20.0, N=400 * 200, lam=1.2)
+    assert r.adjust_actions >= 1
+    assert r.final_sizes == [40, 80, 120, 160]                 # the continuous optimum is integral here: B v_i / sum v
+    assert oracle.minmax_objective(r.final_sizes, v) == oracle.minmax_split_bruteforce(40, [1.0, 2.0, 3.0, 4.0])[0] / 10
+    slow = _sim(t0=[0.0] * 4, v=v, N=400 * 200)
+    assert r.jct < 0.5 * slow.jct                              # 1 s per iteration -> 0.4 s
+    # kill-and-restart removes a persistent straggler; ADJUST_BS alone cannot (its delay does not scale with the batch)
+    kw = dict(persistent_delay=[0.0, 0.0, 4.0, 0.0], N=400 * 2000, decide_every=60.0, L_trans=60.0, L_per=120.0,
+              restart_cost=30.0)
+    bsp, lb, nd = _sim(**kw), _sim(policy=D.ADJUST_BS, **kw), _sim(policy=D.ANTDT_ND, **kw)
+    assert nd.kills == 1 and nd.jct < 0.3 * bsp.jct and lb.kills == 0 and lb.jct > 0.8 * bsp.jct
+
+
+def test_transient_pattern_is_deterministic_and_has_the_stated_rate():
+    from oracle import dds_sim as D
+    hits = sum(D.disturbed(7, w, i, 0.3) for w in range(400) for i in range(10))
+    assert abs(hits / 4000 - 0.3) < 0.03
+    assert [D.disturbed(7, 0, i, 0.3) for i in range(10)] == [D.disturbed(7, 0, i, 0.3) for i in range(10)]
+    assert not any(D.disturbed(7, w, 0, 0.0) for w in range(50)) and all(D.disturbed(7, w, 0, 1.0) for w in range(50))
+    # a burst only delays iterations that start inside it
+    r0 = _sim(N=400 * 4000)
+    r1 = _sim(N=400 * 4000, prob=1.0, intensity=0.5, sleep_duration=1.5, period=1000.0, duration=100.0)
+    assert r1.jct > r0.jct and r1.max_bpt == pytest.approx(0.1 + 0.5 + 0.75)
