@@ -17,9 +17,16 @@ Pins (tests marked "not gpu"): torch-CPU embedding_bag/autograd/Adagrad/Adam as
 library special cases, central finite differences, partition invariance
 (sum_k (B_k/B) g_k equals the whole-batch gradient for any split), row
 sparsity, closed forms of the first Adagrad/Adam step, brute-force coalescing
-and brute-force enumeration of Eq. 3 / Eq. 4.
-Parity unpinned: nothing in this package; the paper prints no worked numeric
-example of an iteration, so no pin is a printed value.
+and brute-force enumeration of Eq. 3 / Eq. 4; for the shard queue its stated
+transitions, at-least-once coverage under random losses and the re-queue order;
+for the job-completion-time model the closed forms of undisturbed, persistently
+disturbed and backup-worker runs, the Eq. 3 split it converges to, and the rate
+of its pseudo-random disturbance pattern.
+Parity unpinned: the paper prints no worked numeric example of an iteration or
+of a schedule, so no pin is a printed value; the decision rules of the
+job-completion-time model beyond those closed forms (window bookkeeping, the
+order of kill and batch-size decisions) are a reading stated in dds_sim.py and
+are pinned only by construction: **parity unpinned** for them.
 """
 from .ps_iteration import (  # noqa: F401
     Model,
