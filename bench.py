@@ -429,7 +429,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the K workers are shards on that device); "
+        sys.exit("bench.py: the library runs on one GPU only (the K workers are shards on that device); "
                  "use --gpus 1")
     if args.workload == "straggler-sim":
         out = run_straggler_sim(args)
