@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import workload as wl
-from helpers import (BF16_MAX_TOL, SMALL, assert_close, assert_step_within_bound, flat_dense_grad, flat_layers, oracle_iteration, per_field, rel_err)
+from helpers import (BF16_MAX_TOL, SMALL, assert_close, assert_step_within_bound, oracle_model, flat_dense_grad, flat_layers, oracle_iteration, per_field, rel_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -306,6 +306,45 @@ def test_validate_batch_reports_bad_ids_and_offsets():
     expect_error(batch.ids, off, 0, "offsets")
     run.set_batch(batch)
     run.ctx.validate_batch()
+
+
+def test_ten_iterations_follow_the_oracle():
+    """State carried from iteration to iteration (tables, accumulators, MLP, the bf16-free fp32
+    path): ten iterations over three rotating batches; losses and final parameters against the
+    oracle.  Rounding differences are fed back through the parameters, so the bound is looser
+    than for one iteration (1e-4; an Adagrad step of an element with |g| ~ eps can differ by up
+    to lr, which the normwise comparison of values absorbs)."""
+    from gpu_helpers import GpuRun
+    from helpers import tables_as_f32
+    cfg = wl.CONFIGS[1]
+    tables, state, flat, fstate, _ = make_inputs(cfg)
+    batches = [wl.make_batch(cfg, i) for i in range(3)]
+    run = GpuRun(cfg, tables, flat, state, fstate, max_batch=cfg.batch, max_shards=cfg.num_shards,
+                 max_nnz=max(int(b.field_ptr[-1]) for b in batches))
+    model = oracle_model(cfg)
+    tabs, st = per_field(cfg, tables_as_f32(cfg, tables).astype(np.float64)), per_field(cfg, state.astype(np.float64))
+    layers = wl.split_params(cfg, flat.astype(np.float64))
+    lstate = wl.split_params(cfg, fstate.astype(np.float64))
+    R = cfg.rows_per_field
+    for it in range(10):
+        b = batches[it % 3]
+        run.set_batch(b)
+        run.iteration(cfg.shard_sizes, batched=True)
+        res = [oracle.worker_step(model, tabs, layers, b, s, n) for s, n in wl.shard_slices(cfg.shard_sizes)]
+        agg = oracle.aggregate(model, b, res)
+        upd = oracle.apply_update(model, tabs, st, layers, lstate, agg)
+        for f in range(cfg.num_fields):
+            tabs[f][agg.unique_ids[f]] = upd.rows[f]
+            st[f][agg.unique_ids[f]] = upd.row_state[f]
+        layers, lstate = upd.layers, upd.layer_state
+        got = run.loss.cpu().numpy()
+        want = np.array([r.loss for r in res])
+        assert np.all(np.abs(got - want) <= 1e-4 * np.abs(want)), f"losses of iteration {it}"
+    assert rel_err(run.params.cpu().numpy(), flat_layers(cfg, layers))[0] <= 1e-4
+    t = run.tables.cpu().numpy()
+    for f in range(cfg.num_fields):
+        assert rel_err(t[f * R:(f + 1) * R], tabs[f])[0] <= 1e-4, f"table {f} after ten iterations"
+        assert rel_err(run.state.cpu().numpy()[f * R:(f + 1) * R], st[f])[0] <= 1e-4
 
 
 def test_single_layer_model():
