@@ -28,13 +28,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # when the counters were taken.
 MEASURED_TRAFFIC = {
     "cfg2": {
-        "gemm_fwd": (73.9e6, "gemm.hip"), "gemm_bwd": (90.9e6, "gemm.hip"), "gemm_wgrad": (185.9e6, "gemm.hip"),
+        "gemm_fwd": (73.7e6, "gemm.hip"), "gemm_bwd": (90.6e6, "gemm.hip"), "gemm_wgrad": (192.8e6, "gemm.hip"),
         "pool": (92.3e6, "embed.hip"),
         "sparse_adagrad": (226.5e6, "coalesce.hip"), "seg_reduce_long": (47.8e6, "coalesce.hip"),
         "dense_adagrad": (100.7e6, "optim.hip"),
     },
-    "sha1": {"gemm.hip": "c2310063890f4b3df1b795fd250c65c7bf00f618",
-             "embed.hip": "8655f3f8f6a057400120d7498ab52e04ca34b47c",
+    "sha1": {"gemm.hip": "02854f0be5c6131691816f640c656ece33427420",
+             "embed.hip": "97e410fb03989b6d85916ea819e8b34f8b3489ab",
              "coalesce.hip": "aa3b71b5e6215f5d4bd08be66afd0377b32ba302",
              "optim.hip": "c63618038b7bd0e4c5f96c1d666ded04e4bbefa3"},
 }
