@@ -36,7 +36,7 @@ MEASURED_TRAFFIC = {
     "sha1": {"gemm.hip": "02854f0be5c6131691816f640c656ece33427420",
              "embed.hip": "97e410fb03989b6d85916ea819e8b34f8b3489ab",
              "coalesce.hip": "aa3b71b5e6215f5d4bd08be66afd0377b32ba302",
-             "optim.hip": "c63618038b7bd0e4c5f96c1d666ded04e4bbefa3"},
+             "optim.hip": "71c2d4e38c79505300b427eea7cd66093b332552"},
 }
 
 
