@@ -35,6 +35,7 @@ class Model:
     bf16_gemm: bool = False           # GEMM operands are bf16 values, accumulation exact here
     lr: float = 0.01
     eps: float = 1e-8
+    mean_pool: bool = False           # bags are averaged instead of summed (empty bag: zeros)
 
 
 def round_bf16(x) -> np.ndarray:
@@ -51,10 +52,11 @@ def round_bf16(x) -> np.ndarray:
 # worker side
 # --------------------------------------------------------------------------
 def embedding_pool(table_f: np.ndarray, ids_f: np.ndarray, offsets_f: np.ndarray,
-                   start: int, length: int) -> np.ndarray:
-    """Sum-pool the bags of samples [start, start+length) of one field.
+                   start: int, length: int, mean: bool = False) -> np.ndarray:
+    """Pool the bags of samples [start, start+length) of one field.
 
-    out[s, :] = sum over the lookups j of bag s, left to right, of table_f[ids_f[j], :].
+    out[s, :] = sum over the lookups j of bag s, left to right, of table_f[ids_f[j], :];
+    with `mean` the sum is divided by the number of lookups of the bag.
     A duplicate id inside a bag counts twice; an empty bag gives zeros.
     """
     D = table_f.shape[1]
@@ -64,17 +66,23 @@ def embedding_pool(table_f: np.ndarray, ids_f: np.ndarray, offsets_f: np.ndarray
     sample = np.repeat(np.arange(length), lens)
     rows = np.asarray(table_f[np.asarray(ids_f[off[0]:off[-1]], dtype=np.int64)], dtype=np.float64)
     np.add.at(out, sample, rows)
+    if mean:
+        out = out / np.maximum(lens, 1)[:, None]
     return out
 
 
-def embedding_pool_loops(table_f, ids_f, offsets_f, start, length) -> np.ndarray:
+def embedding_pool_loops(table_f, ids_f, offsets_f, start, length, mean=False) -> np.ndarray:
     """The same definition as `embedding_pool`, as explicit loops (tiny inputs only)."""
     D = table_f.shape[1]
     out = np.zeros((length, D), dtype=np.float64)
     for s in range(length):
-        for j in range(int(offsets_f[start + s]), int(offsets_f[start + s + 1])):
+        lo, hi = int(offsets_f[start + s]), int(offsets_f[start + s + 1])
+        for j in range(lo, hi):
             for d in range(D):
                 out[s, d] += float(table_f[int(ids_f[j]), d])
+        if mean and hi > lo:
+            for d in range(D):
+                out[s, d] /= (hi - lo)
     return out
 
 
@@ -129,7 +137,7 @@ def worker_step(model: Model, tables: Sequence[np.ndarray], layers, batch,
     x = np.zeros((length, F * D + nd), dtype=np.float64)
     for f in range(F):
         x[:, f * D:(f + 1) * D] = embedding_pool(tables[f], batch.field_ids(f), batch.offsets[f],
-                                                 start, length)
+                                                 start, length, model.mean_pool)
     if nd:
         x[:, F * D:] = np.asarray(batch.dense[start:start + length], dtype=np.float64)
     y = np.asarray(batch.labels[start:start + length], dtype=np.float64)
@@ -159,12 +167,20 @@ def worker_step(model: Model, tables: Sequence[np.ndarray], layers, batch,
 # --------------------------------------------------------------------------
 # server side
 # --------------------------------------------------------------------------
-def shard_weights(lengths: Sequence[int], mask: Optional[Sequence[bool]] = None) -> np.ndarray:
-    """w_k = B_k / sum of the included B_k (0 for an excluded shard)."""
+def shard_weights(lengths: Sequence[int], mask: Optional[Sequence[bool]] = None,
+                  scale: Optional[Sequence[float]] = None) -> np.ndarray:
+    """w_k = c_k * B_k / sum of the included B_k (0 for an excluded shard).
+
+    c_k (default 1) is a per-worker factor on that worker's contribution: the per-worker
+    learning-rate adjustment of the optimization-based methods of Section III (Table II,
+    ADJUST_LR) seen from the server, which applies one update with one learning rate.
+    """
     n = np.asarray(lengths, dtype=np.float64)
     inc = np.ones(len(n), bool) if mask is None else np.asarray(mask, dtype=bool)
     tot = float(n[inc].sum())
     w = np.where(inc, n / tot, 0.0) if tot > 0 else np.zeros(len(n))
+    if scale is not None:
+        w = w * np.asarray(scale, dtype=np.float64)
     return w
 
 
@@ -181,19 +197,21 @@ class Aggregated:
 
 
 def aggregate(model: Model, batch, results: Sequence[ShardResult],
-              mask: Optional[Sequence[bool]] = None, want_samples: bool = False) -> Aggregated:
+              mask: Optional[Sequence[bool]] = None, want_samples: bool = False,
+              scale: Optional[Sequence[float]] = None) -> Aggregated:
     """Server-side aggregation of the included shards' pushed gradients.
 
     Dense: g = sum_k w_k g_k.  Sparse, per field, by direct addressing (no
     sort): count[r] = lookups of row r among the included shards; the rows with
     count > 0 in ascending order are the unique ids, the running sum of their
     counts the segment offsets, and every lookup j of sample s adds
-    w_k * dx_k[s, field slice] into its row, walking samples in global order.
+    w_k * dx_k[s, field slice] into its row, walking samples in global order
+    (divided by the bag's length when the bags are mean-pooled).
     """
     F, D, R = model.num_fields, model.dim, model.rows_per_field
     K = len(results)
     inc = np.ones(K, bool) if mask is None else np.asarray(mask, dtype=bool)
-    w = shard_weights([r.length for r in results], inc)
+    w = shard_weights([r.length for r in results], inc, scale)
     L = len(results[0].dW)
     dW = [sum(w[k] * results[k].dW[l] for k in range(K)) for l in range(L)]
     db = [sum(w[k] * results[k].db[l] for k in range(K)) for l in range(L)]
@@ -219,7 +237,10 @@ def aggregate(model: Model, batch, results: Sequence[ShardResult],
             lo, hi = off[r.start], off[r.start + r.length]
             lens = np.diff(off[r.start:r.start + r.length + 1])
             local = np.repeat(np.arange(r.length), lens)
-            np.add.at(G, pos[ids_f[lo:hi]], w[k] * r.dx[local, f * D:(f + 1) * D])
+            rows = w[k] * r.dx[local, f * D:(f + 1) * D]
+            if model.mean_pool:                 # d(mean of the bag)/d(row) = 1 / bag length
+                rows = rows / np.repeat(lens, lens)[:, None]
+            np.add.at(G, pos[ids_f[lo:hi]], rows)
             if want_samples:
                 for j, s in zip(ids_f[lo:hi], local):
                     seg_s[pos[j]].append(int(r.start + s))

@@ -12,7 +12,7 @@ def oracle_model(cfg: wl.RankingConfig, bf16_gemm=None) -> oracle.Model:
                         tuple(cfg.layer_sizes), cfg.adagrad_state == "rowwise",
                         cfg.table_dtype == "bf16",
                         (cfg.gemm_dtype == "bf16") if bf16_gemm is None else bf16_gemm,
-                        cfg.lr, cfg.eps)
+                        cfg.lr, cfg.eps, cfg.pooling == "mean")
 
 
 def tables_as_f32(cfg, tables):

@@ -4,6 +4,7 @@ Library special cases (torch-CPU embedding_bag / autograd / Adagrad / Adam),
 finite differences, closed forms, invariants of the data-parallel setting
 (Section II: fixed global batch, sum_i B_i = B) and brute force on tiny inputs.
 """
+import dataclasses
 import math
 
 import numpy as np
@@ -36,7 +37,7 @@ def torch_iteration(cfg, tables, flat_params, batch, steps=1, lr=None, eps=None)
         for f in range(F):
             ids = torch.tensor(batch.field_ids(f), dtype=torch.int64)
             off = torch.tensor(batch.offsets[f][:-1], dtype=torch.int64)
-            cols.append(torch.nn.functional.embedding_bag(ids, tabs[f], off, mode="sum"))
+            cols.append(torch.nn.functional.embedding_bag(ids, tabs[f], off, mode=cfg.pooling))
         x = torch.cat(cols + [torch.tensor(batch.dense, dtype=torch.float64)], dim=1)
         h = x
         for l, (W, b) in enumerate(layers):
@@ -67,7 +68,11 @@ def fresh(cfg, batch_index=0, batch=None):
     return tables, state, flat, np.zeros_like(flat), b
 
 
-@pytest.mark.parametrize("cfg", [wl.CONFIGS[1], SMALL], ids=lambda c: c.name)
+SMALL_MEAN = dataclasses.replace(SMALL, name="small-mean", pooling="mean")
+TINY_MEAN = dataclasses.replace(TINY, name="tiny-mean", pooling="mean")
+
+
+@pytest.mark.parametrize("cfg", [wl.CONFIGS[1], SMALL, SMALL_MEAN], ids=lambda c: c.name)
 def test_iteration_matches_torch_whole_batch(cfg):
     """Forward, loss, aggregated gradients and the Adagrad update of a K-shard
     iteration equal torch's whole-batch step (library special case + invariance
@@ -134,8 +139,8 @@ def whole_batch_loss(cfg, tables64, flat64, batch):
     return r.loss, r
 
 
-def test_finite_differences_tiny():
-    cfg = TINY
+@pytest.mark.parametrize("cfg", [TINY, TINY_MEAN], ids=lambda c: c.name)
+def test_finite_differences_tiny(cfg):
     tables, state, flat, fstate, batch = fresh(cfg)
     tables64, flat64 = tables.astype(np.float64), flat.astype(np.float64) * 3.0
     # keep every pre-activation away from the ReLU kink
@@ -221,6 +226,48 @@ def test_masked_shards_are_excluded_and_weights_renormalise():
         assert np.array_equal(agg.unique_ids[f], np.unique(kept))
         assert agg.seg_offsets[f][-1] == len(kept)
     assert_close(agg.dW[0], (4 * res[0].dW[0] + 5 * res[2].dW[0]) / 9, 1e-14)
+
+
+def test_per_worker_scale_is_linear_in_the_single_shard_aggregates():
+    """c_k scales worker k's contribution: the aggregate equals sum_k c_k (B_k/B) A_k, with A_k
+    the aggregate of shard k alone (one-hot mask, weight 1), scattered to the union of rows."""
+    cfg = SMALL
+    tables, state, flat, fstate, batch = fresh(cfg)
+    sizes, scale = (4, 3, 5), (0.5, 1.0, 2.0)
+    model, res, _, _ = oracle_iteration(cfg, tables, state, flat, fstate, batch, sizes)
+    agg = oracle.aggregate(model, batch, res, scale=scale)
+    assert np.allclose(agg.weights, [0.5 * 4 / 12, 3 / 12, 2.0 * 5 / 12], rtol=1e-15)
+    R, D = cfg.rows_per_field, cfg.dim
+    single = [oracle.aggregate(model, batch, res, mask=[j == k for j in range(3)]) for k in range(3)]
+    for l in range(len(agg.dW)):
+        want = sum(scale[k] * sizes[k] / 12 * single[k].dW[l] for k in range(3))
+        assert_close(agg.dW[l], want, 1e-13, f"dW{l}")
+    for f in range(cfg.num_fields):
+        want = np.zeros((R, D))
+        for k in range(3):
+            want[single[k].unique_ids[f]] += scale[k] * sizes[k] / 12 * single[k].G[f]
+        got = np.zeros((R, D))
+        got[agg.unique_ids[f]] = agg.G[f]
+        assert_close(got, want, 1e-13, f"G{f}")
+    # all factors equal to c: c times the plain aggregate
+    half = oracle.aggregate(model, batch, res, scale=(0.5,) * 3)
+    plain = oracle.aggregate(model, batch, res)
+    assert_close(half.G[0], 0.5 * plain.G[0], 1e-15)
+
+
+def test_mean_pool_loops_and_library():
+    cfg = SMALL_MEAN
+    tables, _, _, _, batch = fresh(cfg)
+    R = cfg.rows_per_field
+    a = oracle.embedding_pool(tables[:R], batch.field_ids(0), batch.offsets[0], 2, 9, mean=True)
+    b = oracle.embedding_pool_loops(tables[:R], batch.field_ids(0), batch.offsets[0], 2, 9, mean=True)
+    assert_close(a, b, 1e-15)
+    t = torch.nn.functional.embedding_bag(torch.tensor(batch.field_ids(0), dtype=torch.int64),
+                                          torch.tensor(tables[:R], dtype=torch.float64),
+                                          torch.tensor(batch.offsets[0][:-1], dtype=torch.int64), mode="mean")
+    assert_close(a, t.numpy()[2:11], 1e-15)
+    lens = np.diff(batch.offsets[0])
+    assert (lens == 0).any() and np.all(a[lens[2:11] == 0] == 0.0)   # an empty bag pools to zeros
 
 
 # --------------------------------------------------------------- coalescing

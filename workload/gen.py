@@ -42,6 +42,7 @@ class RankingConfig:
     min_bag: int = 1
     lr: float = 0.01
     eps: float = 1e-8
+    pooling: str = "sum"      # "sum" | "mean"
 
     @property
     def batch(self) -> int:
