@@ -54,6 +54,7 @@ enum {
 
 enum { ANTDT_F32 = 0, ANTDT_BF16 = 1 };
 enum { ANTDT_STATE_ELEMENTWISE = 0, ANTDT_STATE_ROWWISE = 1 };
+enum { ANTDT_POOL_SUM = 0, ANTDT_POOL_MEAN = 1 };
 
 typedef struct antdt_ctx antdt_ctx; /* opaque; holds host metadata only */
 
@@ -87,6 +88,9 @@ typedef struct antdt_model {
   int32_t max_shards;       /* K_max, 1..ANTDT_MAX_SHARDS */
   int64_t max_batch;        /* largest global batch B */
   int64_t max_nnz;          /* largest total number of lookups (all fields) of one batch */
+  int32_t pooling;          /* ANTDT_POOL_SUM: a bag is the sum of its rows.  ANTDT_POOL_MEAN: the sum
+                               divided by the number of lookups of the bag (an empty bag is zeros);
+                               each looked-up row then receives dX / bag length as its gradient */
 } antdt_model;
 
 /* Create / destroy a context.  Host work only.  INVALID_ARG on an inconsistent model. */
@@ -201,6 +205,19 @@ int antdt_apply_update(antdt_ctx* ctx, void* stream);
  * Host only.
  */
 int antdt_set_lr(antdt_ctx* ctx, float lr);
+
+/*
+ * Per-worker factors c_k on the aggregation weights: w_k = c_k * B_k / sum_{included} B_j.  The
+ * optimization-based methods of Section III (ADJUST_LR in Table II) give each worker a learning
+ * rate of its own that penalises the lagging ones; with one server-side update this is a factor
+ * on that worker's gradient.  The factors are not renormalised.  scale: host array of K values,
+ * finite and >= 0; NULL resets all factors to 1 (the state after antdt_create).  They stay in
+ * force until changed, also across antdt_set_batch and antdt_assign_shard (a worker index
+ * beyond the K given here has factor 1).  May be called at any point before antdt_aggregate; when
+ * it comes after antdt_worker_step_all, that aggregate rebuilds the lookup weights on its stream
+ * instead of using the ones prepared beside the worker step.  Host only.
+ */
+int antdt_set_shard_scale(antdt_ctx* ctx, const double* scale, int32_t K);
 
 /*
  * Plan for heterogeneous dedicated devices with gradient accumulation (Section VI-B, Eq. 4).

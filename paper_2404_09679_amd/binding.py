@@ -14,6 +14,7 @@ MAX_LAYERS, MAX_FIELDS, MAX_SHARDS = 8, 128, 64
 F32, BF16 = 0, 1
 INFEASIBLE = -6
 ELEMENTWISE, ROWWISE = 0, 1
+POOL_SUM, POOL_MEAN = 0, 1
 
 EXPORTS = [
     "antdt_create", "antdt_destroy", "antdt_last_error", "antdt_workspace_bytes", "antdt_bind",
@@ -22,6 +23,7 @@ EXPORTS = [
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
     "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr", "antdt_validate_batch",
+    "antdt_set_shard_scale",
     "antdt_dds_create", "antdt_dds_destroy", "antdt_dds_num_shards", "antdt_dds_fetch", "antdt_dds_report_done",
     "antdt_dds_release_worker", "antdt_dds_shard", "antdt_dds_counts", "antdt_simulate_bsp",
 ]
@@ -40,6 +42,7 @@ class Model(C.Structure):
         ("num_layers", C.c_int32), ("layer_sizes", C.c_int32 * (MAX_LAYERS + 1)),
         ("gemm_dtype", C.c_int32), ("lr", C.c_float), ("eps", C.c_float),
         ("max_shards", C.c_int32), ("max_batch", C.c_int64), ("max_nnz", C.c_int64),
+        ("pooling", C.c_int32),
     ]
 
 
@@ -91,6 +94,7 @@ def _load():
     lib.antdt_kernel_name.argtypes = [i32]
     lib.antdt_kernel_name.restype = C.c_char_p
     lib.antdt_set_lr.argtypes = [vp, f32]
+    lib.antdt_set_shard_scale.argtypes = [vp, C.POINTER(C.c_double), i32]
     lib.antdt_validate_batch.argtypes = [vp, vp]
     lib.antdt_dds_create.argtypes = [i64, i64, i32, C.POINTER(vp)]
     lib.antdt_dds_destroy.argtypes = [vp]
@@ -138,6 +142,7 @@ def model_from_config(cfg, max_batch: Optional[int] = None, max_nnz: Optional[in
     m.max_shards = max_shards or max(1, len(cfg.shard_sizes))
     m.max_batch = max_batch or max(1, sum(cfg.shard_sizes))
     m.max_nnz = max_nnz if max_nnz is not None else m.max_batch * cfg.max_bag * cfg.num_fields
+    m.pooling = POOL_MEAN if getattr(cfg, "pooling", "sum") == "mean" else POOL_SUM
     return m
 
 
@@ -236,6 +241,13 @@ class Context:
 
     def set_lr(self, lr: float):
         self._check(lib.antdt_set_lr(self._h, lr))
+
+    def set_shard_scale(self, scale: Optional[Sequence[float]]):
+        if scale is None:
+            self._check(lib.antdt_set_shard_scale(self._h, None, 0))
+        else:
+            arr = (C.c_double * len(scale))(*[float(v) for v in scale])
+            self._check(lib.antdt_set_shard_scale(self._h, arr, len(scale)))
 
     def apply_update(self):
         self._check(lib.antdt_apply_update(self._h, _stream()))

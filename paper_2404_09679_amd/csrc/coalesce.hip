@@ -329,10 +329,21 @@ struct Row4 {
   float v[4];
 };
 
-// g += w(sample) * dX[sample, field slice] over sorted entries [b, e) taken with stride `step`,
-// NF entries in flight (added in order).
-template <int NF = 4>
-__device__ __forceinline__ void accumulate_run(const SegArgs& a, const float* dxcol, int b, int e, int step, Row4& g) {
+// Weight of one lookup of sample s: the shard weight, divided by the length of the sample's bag
+// in this field when the bags are mean-pooled (the bag is not empty: the lookup is in it).
+template <bool MEAN>
+__device__ __forceinline__ float lookup_weight(const SegArgs& a, const int32_t* off, int s) {
+  const float w = a.sample_w[s];
+  if (!MEAN) return w;
+  return w / (float)max(off[s + 1] - off[s], 1);
+}
+
+// g += w(lookup) * dX[sample, field slice] over sorted entries [b, e) of field f taken with
+// stride `step`, NF entries in flight (added in order).
+template <bool MEAN, int NF = 4>
+__device__ __forceinline__ void accumulate_run(const SegArgs& a, int f, int c, int b, int e, int step, Row4& g) {
+  const float* dxcol = a.dx + f * a.D + c * 4;
+  const int32_t* off = MEAN ? a.offsets + (int64_t)f * (a.B + 1) : nullptr;
   int i = b;
   for (; i + (NF - 1) * step < e; i += NF * step) {
     int s[NF];
@@ -342,7 +353,7 @@ __device__ __forceinline__ void accumulate_run(const SegArgs& a, const float* dx
     float4 x[NF];
 #pragma unroll
     for (int q = 0; q < NF; ++q) {
-      w[q] = a.sample_w[s[q]];
+      w[q] = lookup_weight<MEAN>(a, off, s[q]);
       x[q] = *reinterpret_cast<const float4*>(dxcol + (int64_t)s[q] * a.lddx);
     }
 #pragma unroll
@@ -355,7 +366,7 @@ __device__ __forceinline__ void accumulate_run(const SegArgs& a, const float* dx
   }
   for (; i < e; i += step) {
     const int s = min(max(a.pay[i], 0), a.B - 1);
-    const float w = a.sample_w[s];
+    const float w = lookup_weight<MEAN>(a, off, s);
     const float4 x = *reinterpret_cast<const float4*>(dxcol + (int64_t)s * a.lddx);
     g.v[0] = fmaf(w, x.x, g.v[0]);
     g.v[1] = fmaf(w, x.y, g.v[1]);
@@ -418,7 +429,7 @@ __device__ __forceinline__ void load_row(const SegArgs& a, int64_t row, int c, f
 // `UPDATE`, the Adagrad step of the row is applied at once (the coalesced gradient never
 // goes to memory); otherwise the sum is written to G.  Runs longer than the threshold are
 // cut into chunks that are queued for the block kernel below.
-template <typename TT, bool ROWWISE, bool UPDATE>
+template <typename TT, bool ROWWISE, bool UPDATE, bool MEAN>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a) {
   const int lps = a.D >> 2;
   const int U = a.ubase[a.F];
@@ -450,7 +461,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a) {
     float srow0 = 0.f;
     if (UPDATE) load_row<TT, ROWWISE>(a, row, c, p0, s0, srow0);
     Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
-    accumulate_run(a, a.dx + f * a.D + c * 4, b, e, 1, gsum);
+    accumulate_run<MEAN>(a, f, c, b, e, 1, gsum);
     if (UPDATE) adagrad_row<TT, ROWWISE>(a, row, c, lps, gsum, p0, s0, srow0);
     else *reinterpret_cast<float4*>(a.G + u * a.D + c * 4) = make_float4(gsum.v[0], gsum.v[1], gsum.v[2], gsum.v[3]);
   }
@@ -458,6 +469,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a) {
 
 // One block per chunk of a long run: the lane groups stride over the chunk, then their
 // partial sums are added in group order (fixed order: repeatable bit for bit).
+template <bool MEAN>
 __global__ __launch_bounds__(256) void seg_chunk_kernel(SegArgs a) {
   __shared__ float4 red[256];
   const int lps = a.D >> 2;
@@ -469,7 +481,7 @@ __global__ __launch_bounds__(256) void seg_chunk_kernel(SegArgs a) {
     const int b = a.segabs[u] + q * a.chunk, e = min(a.segabs[u + 1], b + a.chunk);
     const int f = a.ufield[u];
     Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
-    accumulate_run(a, a.dx + f * a.D + c * 4, b + g, e, ngroups, gsum);
+    accumulate_run<MEAN>(a, f, c, b + g, e, ngroups, gsum);
     red[threadIdx.x] = make_float4(gsum.v[0], gsum.v[1], gsum.v[2], gsum.v[3]);
     __syncthreads();
     for (int half = ngroups >> 1; half > 0; half >>= 1) {
@@ -522,17 +534,23 @@ __global__ __launch_bounds__(256) void seg_finish_kernel(SegArgs a) {
   }
 }
 
-template <typename TT, bool ROWWISE, bool UPDATE>
-void launch_reduce_variant(const SegArgs& a, unsigned blocks, Profiler* prof, hipStream_t s) {
+template <typename TT, bool ROWWISE, bool UPDATE, bool MEAN>
+void launch_reduce_pooling(const SegArgs& a, unsigned blocks, Profiler* prof, hipStream_t s) {
   {
     ProfScope ps(prof, UPDATE ? KID_SPARSE_ADAGRAD : KID_SEG_REDUCE, s);
-    hipLaunchKernelGGL((seg_reduce_kernel<TT, ROWWISE, UPDATE>), dim3(blocks), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((seg_reduce_kernel<TT, ROWWISE, UPDATE, MEAN>), dim3(blocks), dim3(256), 0, s, a);
   }
   {
     ProfScope ps(prof, KID_SEG_REDUCE_LONG, s);
-    hipLaunchKernelGGL(seg_chunk_kernel, dim3(2048), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(seg_chunk_kernel<MEAN>, dim3(2048), dim3(256), 0, s, a);
     hipLaunchKernelGGL((seg_finish_kernel<TT, ROWWISE, UPDATE>), dim3(64), dim3(256), 0, s, a);
   }
+}
+
+template <typename TT, bool ROWWISE, bool UPDATE>
+void launch_reduce_variant(const SegArgs& a, unsigned blocks, Profiler* prof, hipStream_t s) {
+  if (a.mean_pool) launch_reduce_pooling<TT, ROWWISE, UPDATE, true>(a, blocks, prof, s);
+  else launch_reduce_pooling<TT, ROWWISE, UPDATE, false>(a, blocks, prof, s);
 }
 
 }  // namespace

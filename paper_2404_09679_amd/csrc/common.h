@@ -108,6 +108,7 @@ struct PoolArgs {
   int32_t F, D, num_dense, ldx, B, s0, ns;
   int64_t R, ldt;
   int32_t table_bf16, x_bf16;
+  int32_t mean_pool;      // divide every bag's sum by its number of lookups
 };
 hipError_t launch_pool(const PoolArgs& a, const FieldPtr& fp, hipStream_t s);
 hipError_t launch_validate(const int32_t* ids, const int32_t* offsets, const FieldPtr& fp, int64_t B, int64_t R, int F,
@@ -244,6 +245,8 @@ struct SegArgs {
   float* G;                        // [U, D] coalesced gradient (written when not updating)
   const float* dx;                 // [B, lddx]
   int64_t lddx;
+  const int32_t* offsets;          // [F][B + 1] bag boundaries of the batch (read when mean_pool)
+  int32_t mean_pool;               // bags are averaged: a lookup's gradient is dX / bag length
   int32_t F, D, B, max_tiles, total_tiles, long_threshold, chunk, long_cap, item_cap;
   // parameter update fused into the reduction (update != 0)
   int32_t update, table_bf16, rowwise;

@@ -141,6 +141,8 @@ struct antdt_ctx {
   int64_t shard_B = 0;
   bool stepped[ANTDT_MAX_SHARDS] = {};
   bool included[ANTDT_MAX_SHARDS] = {};
+  double shard_scale[ANTDT_MAX_SHARDS];  // per-worker factor on the aggregation weight (1 unless set)
+  bool weights_dirty = false;            // the factors changed after the weights were last formed
   int sorted_buf = 0;
   // side stream on which the coalescing structure of a batch is built while the MLP runs
   hipStream_t side = nullptr;
@@ -258,10 +260,12 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
   if (m.max_shards < 1 || m.max_shards > ANTDT_MAX_SHARDS) return bad("max_shards out of range");
   if (m.max_batch < 1 || m.max_batch >= (1ll << 31)) return bad("max_batch out of range");
   if (m.max_nnz < 0 || m.max_nnz >= (1ll << 31) - 4096) return bad("max_nnz out of range");
+  if (m.pooling != ANTDT_POOL_SUM && m.pooling != ANTDT_POOL_MEAN) return bad("pooling: ANTDT_POOL_SUM or ANTDT_POOL_MEAN");
   if (!(m.lr >= 0.f) || !(m.eps > 0.f)) return bad("lr must be >= 0 and eps > 0");
 
   antdt_ctx* c = new antdt_ctx();
   c->m = m;
+  for (int k = 0; k < ANTDT_MAX_SHARDS; ++k) c->shard_scale[k] = 1.0;
   c->L = m.num_layers;
   c->FD = m.num_fields * m.dim;
   c->in0 = m.layer_sizes[0];
@@ -527,6 +531,7 @@ static void fill_seg_args(antdt_ctx* c, SegArgs& a) {
   a.segabs = c->segabs; a.segoff = c->segoff; a.sample_w = c->sample_w; a.counters = c->counters;
   a.long_seg = c->long_seg; a.items = c->items; a.partial = c->partial;
   a.G = c->G; a.dx = c->dx; a.lddx = c->FD;
+  a.offsets = c->offsets; a.mean_pool = m.pooling == ANTDT_POOL_MEAN;
   a.F = m.num_fields; a.D = m.dim; a.B = (int32_t)c->B; a.max_tiles = c->amax_tiles;
   a.total_tiles = c->atotal_tiles; a.long_threshold = c->long_threshold; a.chunk = c->chunk;
   a.long_cap = (int32_t)c->long_cap; a.item_cap = (int32_t)c->item_cap;
@@ -546,7 +551,9 @@ static void set_weights(antdt_ctx* c) {
   for (int k = 0; k < K; ++k)
     if (c->included[k]) tot += c->tab.len[k];
   for (int k = 0; k < ANTDT_MAX_SHARDS; ++k)
-    c->tab.w[k] = (k < K && c->included[k] && tot > 0) ? (float)((double)c->tab.len[k] / (double)tot) : 0.0f;
+    c->tab.w[k] = (k < K && c->included[k] && tot > 0)
+                      ? (float)(c->shard_scale[k] * ((double)c->tab.len[k] / (double)tot)) : 0.0f;
+  c->weights_dirty = false;
 }
 
 // Sort the lookups by row id, find the runs, and fill the per-sample weights: everything of
@@ -607,6 +614,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     a.F = m.num_fields; a.D = m.dim; a.num_dense = m.num_dense; a.ldx = c->ldx; a.B = (int32_t)c->B;
     a.s0 = (int32_t)s0; a.ns = (int32_t)ns; a.R = m.rows_per_field;
     a.table_bf16 = m.table_dtype == ANTDT_BF16; a.x_bf16 = c->act_bf16;
+    a.mean_pool = m.pooling == ANTDT_POOL_MEAN;
     a.xt = c->act_bf16 ? c->act_t[0] : nullptr; a.ldt = c->ldt; a.lookup_sample = c->lookup_sample;
     ProfScope ps(pr, KID_POOL, s);
     HIP_TRY(c, launch_pool(a, c->fp, s));
@@ -805,7 +813,7 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
   bool all = true;  // leaving out an empty shard changes nothing
   for (int k = 0; k < K; ++k) all = all && (c->included[k] || c->tab.len[k] == 0);
   if (c->presorted) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
-  if (c->presorted && all) {
+  if (c->presorted && all && !c->weights_dirty) {
     // the batched worker step already built the structure on the side stream
   } else if (all) {
     set_weights(c);
@@ -840,6 +848,18 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
   c->g_valid = false;
   c->gdense_valid = false;  // the dense sum is formed inside the optimizer kernel (or on request)
   c->stage = ST_AGGREGATED;
+  return ANTDT_OK;
+}
+
+int antdt_set_shard_scale(antdt_ctx* c, const double* scale, int32_t K) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_shard_scale: null context");
+  if (scale && (K < 1 || K > c->m.max_shards)) return fail(c, ANTDT_INVALID_ARG, "antdt_set_shard_scale: K out of range");
+  if (scale)
+    for (int k = 0; k < K; ++k)
+      if (!(scale[k] >= 0.0) || !isfinite(scale[k]))
+        return fail(c, ANTDT_INVALID_ARG, "antdt_set_shard_scale: factors must be finite and >= 0");
+  for (int k = 0; k < ANTDT_MAX_SHARDS; ++k) c->shard_scale[k] = (scale && k < K) ? scale[k] : 1.0;
+  c->weights_dirty = true;  // an aggregation structure built ahead of time carries the old weights
   return ANTDT_OK;
 }
 

@@ -1,4 +1,4 @@
-// Embedding-bag gather and sum-pool (worker side of the iteration, Section II:
+// Embedding-bag gather and sum- or mean-pool (worker side of the iteration, Section II:
 // the forward pass on the local batch B_k), plus the procedural table fill.
 #include <algorithm>
 
@@ -115,6 +115,11 @@ __global__ __launch_bounds__(256) void pool_tile_kernel(PoolArgs a, FieldPtr fp)
           for (int e = 0; e < EV; ++e) acc[e] += v[q].get(e);
         }
     }
+    if (a.mean_pool && end - begin > 1) {
+      const float len = (float)(end - begin);
+#pragma unroll
+      for (int e = 0; e < EV; ++e) acc[e] /= len;
+    }
     if (valid) {
       store_row<OT, EV>(reinterpret_cast<OT*>(a.x) + s * a.ldx + f * a.D + c * EV, acc);
       if (a.xt) {
@@ -173,6 +178,11 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolArgs a, FieldPtr fp) {
   for (int o = lpr; o < 64; o <<= 1) {
 #pragma unroll
     for (int e = 0; e < EV; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+  }
+  if (a.mean_pool && end - begin > 1) {
+    const float len = (float)(end - begin);
+#pragma unroll
+    for (int e = 0; e < EV; ++e) acc[e] /= len;
   }
   if (sub == 0) {
     store_row<OT, EV>(xrow + f * a.D + c * EV, acc);

@@ -50,9 +50,12 @@ class GpuRun:
         self.d_labels = torch.from_numpy(batch.labels).to(DEV)
         self.ctx.set_batch(self.d_ids, batch.field_ptr, self.d_off, self.d_dense, self.d_labels)
 
-    def iteration(self, sizes, batched=False, mask=None, update=True):
+    def iteration(self, sizes, batched=False, mask=None, update=True, scale=None, scale_late=False):
+        """`scale`: per-worker factors, set before the worker steps or (`scale_late`) after them."""
         K = len(sizes)
         self.ctx.assign_shard(self.batch.batch, K, sizes=sizes)
+        if not scale_late:
+            self.ctx.set_shard_scale(scale)
         self.loss = torch.zeros(K, dtype=torch.float32, device=DEV)
         if batched:
             self.ctx.worker_step_all(self.loss)
@@ -66,6 +69,8 @@ class GpuRun:
             x = self.ctx.view_pooled(k).float().cpu().numpy()
             dense, dx = self.ctx.view_shard_grads(k)
             self.shard_out.append((x, dense.cpu().numpy().copy(), dx.cpu().numpy().copy()))
+        if scale_late:
+            self.ctx.set_shard_scale(scale)
         self.ctx.aggregate(mask)
         torch.cuda.synchronize()
         self.g_dense = self.ctx.view_dense_grad().cpu().numpy().copy()

@@ -26,7 +26,7 @@ def per_field(cfg, arr):
 
 
 def oracle_iteration(cfg, tables_f32, state, flat_params, flat_state, batch, sizes,
-                     mask=None, bf16_gemm=None, want_samples=False):
+                     mask=None, bf16_gemm=None, want_samples=False, scale=None):
     """Run worker_step for every shard, aggregate and apply_update with the oracle."""
     model = oracle_model(cfg, bf16_gemm)
     tabs = per_field(cfg, tables_f32)
@@ -34,7 +34,7 @@ def oracle_iteration(cfg, tables_f32, state, flat_params, flat_state, batch, siz
     layers = wl.split_params(cfg, flat_params)
     lstate = wl.split_params(cfg, flat_state)
     res = [oracle.worker_step(model, tabs, layers, batch, s, n) for s, n in wl.shard_slices(sizes)]
-    agg = oracle.aggregate(model, batch, res, mask, want_samples)
+    agg = oracle.aggregate(model, batch, res, mask, want_samples, scale)
     upd = oracle.apply_update(model, tabs, st, layers, lstate, agg)
     return model, res, agg, upd
 

@@ -51,7 +51,7 @@ def make_inputs(cfg, nonzero_state=False, batch_index=0):
 
 
 def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, fwd_tol=None,
-                    bf16_gemm_oracle=None, batch_index=0, mask=None):
+                    bf16_gemm_oracle=None, batch_index=0, mask=None, scale=None, scale_late=False):
     """Run one full iteration on the GPU and with the oracle; compare every result.
     `tol` bounds gradients and updates, `fwd_tol` (default: tol) the forward results."""
     from gpu_helpers import GpuRun
@@ -59,10 +59,10 @@ def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, f
     tables, state, flat, fstate, batch = make_inputs(cfg, nonzero_state, batch_index)
     t32 = tables_as_f32(cfg, tables)
     model, res, agg, upd = oracle_iteration(cfg, t32, state, flat, fstate, batch, sizes,
-                                            mask=mask, bf16_gemm=bf16_gemm_oracle, want_samples=True)
+                                            mask=mask, bf16_gemm=bf16_gemm_oracle, want_samples=True, scale=scale)
     run = GpuRun(cfg, tables, flat, state, fstate, max_batch=batch.batch, max_shards=len(sizes))
     run.set_batch(batch)
-    run.iteration(sizes, batched=batched, mask=mask)
+    run.iteration(sizes, batched=batched, mask=mask, scale=scale, scale_late=scale_late)
     F, D, R = cfg.num_fields, cfg.dim, cfg.rows_per_field
     W = cfg.input_width
     fwd_tol = tol if fwd_tol is None else fwd_tol
@@ -184,6 +184,45 @@ def test_masked_aggregation_leaves_shards_out():
     check_iteration(MID, MID.shard_sizes, mask=tuple(int(k == K - 1) for k in range(K)))
     check_iteration(ROW_BF, ROW_BF.shard_sizes, mask=tuple(int(k != 0) for k in range(len(ROW_BF.shard_sizes))),
                     tol=TOLBF, bf16_gemm_oracle=True)
+
+
+def test_per_worker_factors_on_the_aggregation_weights():
+    """Table II, ADJUST_LR (Section III: a learning rate per worker that penalises the lagging
+    ones): w_k = c_k B_k / B, set before the worker steps, after a batched step (the prepared
+    lookup weights are rebuilt), together with a mask, and reset."""
+    cfg = wl.CONFIGS[1]
+    check_iteration(cfg, cfg.shard_sizes, scale=(1.0, 0.25, 2.0, 0.5))
+    check_iteration(cfg, cfg.shard_sizes, scale=(1.0, 0.25, 2.0, 0.5), batched=True)
+    check_iteration(cfg, cfg.shard_sizes, scale=(0.5, 1.0, 0.0, 1.5), batched=True, scale_late=True, nonzero_state=True)
+    check_iteration(SMALL, (3, 4, 0, 5), scale=(2.0, 1.0, 1.0, 0.5), mask=(1, 0, 1, 1))
+    K = len(MID.shard_sizes)
+    check_iteration(MID, MID.shard_sizes, scale=tuple(0.5 + 0.5 * k for k in range(K)), batched=True)
+    # back to factors of 1: the plain iteration again
+    from gpu_helpers import GpuRun
+    tables, state, flat, fstate, batch = make_inputs(cfg)
+    run = GpuRun(cfg, tables, flat, state, fstate, max_batch=batch.batch, max_shards=len(cfg.shard_sizes))
+    run.set_batch(batch)
+    run.iteration(cfg.shard_sizes, batched=True, scale=(3.0, 3.0, 3.0, 3.0), update=False)
+    g3 = run.g_dense.copy()
+    run.iteration(cfg.shard_sizes, batched=True, scale=None, update=False)
+    assert_close(g3, 3.0 * run.g_dense, TOL32, "three times the plain aggregate")
+    with pytest.raises(Exception):
+        run.ctx.set_shard_scale((1.0, -1.0))
+
+
+@pytest.mark.parametrize("base", ["config1", "small", "mid", "mid-bf16", "rowwise-bf16"])
+def test_mean_pooled_bags(base):
+    """Bags averaged instead of summed: the pooled input is the bag mean (an empty bag zeros) and
+    every looked-up row receives dX / bag length."""
+    import dataclasses
+    src = {"config1": wl.CONFIGS[1], "small": SMALL, "mid": MID, "mid-bf16": MID_BF, "rowwise-bf16": ROW_BF}[base]
+    cfg = dataclasses.replace(src, name=src.name + "-mean", pooling="mean")
+    if cfg.gemm_dtype == "bf16":
+        check_iteration(cfg, cfg.shard_sizes, batched=True, tol=TOLBF, bf16_gemm_oracle=True)
+    else:
+        check_iteration(cfg, cfg.shard_sizes, batched=(base != "small"))
+        if base == "small":
+            check_iteration(cfg, (3, 4, 0, 5), mask=(1, 0, 1, 1))
 
 
 def test_masked_then_full_aggregation_of_the_same_batch():

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_model_struct_matches_header_layout():
     # int32, (pad), int64, 4 x int32 ... : the ctypes mirror must have the C layout
-    assert C.sizeof(A.Model) == 104
+    assert C.sizeof(A.Model) == 112 and A.Model.pooling.offset == 104
     assert A.Model.rows_per_field.offset == 8 and A.Model.layer_sizes.offset == 36
     assert A.Model.max_batch.offset == 88 and A.Model.max_nnz.offset == 96
 
@@ -36,10 +36,20 @@ def good_model():
     return A.model_from_config(wl.CONFIGS[1])
 
 
+def test_shard_scale_arguments():
+    ctx = A.Context(good_model())
+    ctx.set_shard_scale((1.0, 0.5, 0.0, 2.0))
+    ctx.set_shard_scale(None)
+    for bad in [(1.0, -0.5), (float("nan"),), (float("inf"), 1.0), (1.0,) * 5]:
+        with pytest.raises(A.AntdtError) as e:
+            ctx.set_shard_scale(bad)
+        assert e.value.code == -1 and "antdt_set_shard_scale" in str(e.value)
+
+
 @pytest.mark.parametrize("field,value", [("num_fields", 0), ("num_fields", 129), ("rows_per_field", 0),
                                          ("dim", 6), ("dim", 3), ("dim", 512), ("table_dtype", 2), ("num_layers", 0),
                                          ("num_layers", 9), ("max_shards", 65), ("max_batch", 0), ("eps", 0.0),
-                                         ("num_dense", 12)])
+                                         ("num_dense", 12), ("pooling", 2), ("pooling", -1)])
 def test_create_rejects_bad_models(field, value):
     m = good_model()
     setattr(m, field, value)
