@@ -338,6 +338,15 @@ int antdt_dense_aggregate_adam(float* p, float* m, float* v, const float* const*
                                double beta2, double eps, int64_t step, void* stream);
 
 /*
+ * Plain streaming copy dst[i] = src[i], i < n (measurement aid, not part of the iteration): the
+ * bandwidth this kernel reaches on a large buffer is the practical ceiling that the memory-bound
+ * kernels of the iteration are compared with, and its known traffic (4n bytes read, 4n written)
+ * calibrates the profiler's HBM byte counters.  dst, src: DEVICE, 16-byte aligned, not
+ * overlapping; 0 <= n < 2^40.  Enqueues one kernel on `stream`.  Context-free.
+ */
+int antdt_stream_copy(float* dst, const float* src, int64_t n, void* stream);
+
+/*
  * Fill embedding tables with their procedural initial values (input generation, not part
  * of the iteration): value(f, r, d) = scale * (u * 2^-23 - 1), u = top 24 bits of
  * fmix32(fmix32(r + 0x9E3779B9*(f+1)) ^ (0x85EBCA6B*(d+1))), fmix32 = MurmurHash3's 32-bit

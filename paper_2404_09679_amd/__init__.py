@@ -18,4 +18,5 @@ from .binding import (  # noqa: F401
     lib,
     model_from_config,
     plan_accumulation,
+    stream_copy,
 )

@@ -23,7 +23,7 @@ EXPORTS = [
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
     "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr", "antdt_validate_batch",
-    "antdt_set_shard_scale",
+    "antdt_set_shard_scale", "antdt_stream_copy",
     "antdt_dds_create", "antdt_dds_destroy", "antdt_dds_num_shards", "antdt_dds_fetch", "antdt_dds_report_done",
     "antdt_dds_release_worker", "antdt_dds_shard", "antdt_dds_counts", "antdt_simulate_bsp",
 ]
@@ -95,6 +95,7 @@ def _load():
     lib.antdt_kernel_name.restype = C.c_char_p
     lib.antdt_set_lr.argtypes = [vp, f32]
     lib.antdt_set_shard_scale.argtypes = [vp, C.POINTER(C.c_double), i32]
+    lib.antdt_stream_copy.argtypes = [vp, vp, i64, vp]
     lib.antdt_validate_batch.argtypes = [vp, vp]
     lib.antdt_dds_create.argtypes = [i64, i64, i32, C.POINTER(vp)]
     lib.antdt_dds_destroy.argtypes = [vp]
@@ -322,6 +323,17 @@ def dense_aggregate_adam(p, m, v, grads: Sequence[torch.Tensor], weights: Sequen
 def fill_tables(tables: torch.Tensor, num_fields: int, rows_per_field: int, dim: int, scale: float = 0.05):
     dt = BF16 if tables.dtype == torch.bfloat16 else F32
     rc = lib.antdt_fill_tables(_ptr(tables), dt, num_fields, rows_per_field, dim, scale, _stream())
+    if rc:
+        raise AntdtError(rc, lib.antdt_last_error(None).decode())
+
+
+def stream_copy(dst: torch.Tensor, src: torch.Tensor):
+    """dst[:] = src with the library's plain copy kernel (fp32, contiguous, same length)."""
+    if dst.dtype != torch.float32 or src.dtype != torch.float32 or dst.numel() != src.numel():
+        raise ValueError("stream_copy: two float32 tensors of one length")
+    if not (dst.is_contiguous() and src.is_contiguous() and dst.is_cuda and src.is_cuda):
+        raise ValueError("stream_copy: contiguous device tensors")
+    rc = lib.antdt_stream_copy(_ptr(dst), _ptr(src), dst.numel(), _stream())
     if rc:
         raise AntdtError(rc, lib.antdt_last_error(None).decode())
 

@@ -305,5 +305,6 @@ struct AdamArgs {
   float lr, b1, b2, c1, c2, eps, inv_bc1, inv_bc2;  // c = 1 - b, formed in double on the host
 };
 hipError_t launch_adam(const AdamArgs& a, hipStream_t s);
+hipError_t launch_stream_copy(float* dst, const float* src, int64_t n, hipStream_t s);
 
 }  // namespace antdt

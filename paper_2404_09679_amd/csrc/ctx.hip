@@ -960,6 +960,13 @@ int antdt_dense_aggregate_adam(float* p, float* mm, float* v, const float* const
   return ANTDT_OK;
 }
 
+int antdt_stream_copy(float* dst, const float* src, int64_t n, void* stream) {
+  if (n < 0 || n >= (1ll << 40) || (n > 0 && (!dst || !src)) || (((uintptr_t)dst | (uintptr_t)src) & 15))
+    return fail(nullptr, ANTDT_INVALID_ARG, "antdt_stream_copy: null or misaligned pointer, or n out of range");
+  HIP_TRY(nullptr, launch_stream_copy(dst, src, n, (hipStream_t)stream));
+  return ANTDT_OK;
+}
+
 int antdt_fill_tables(void* tables, int32_t dtype, int32_t F, int64_t R, int32_t D, float scale, void* stream) {
   if (!tables || F < 1 || R < 1 || D < 1 || (dtype != ANTDT_F32 && dtype != ANTDT_BF16))
     return fail(nullptr, ANTDT_INVALID_ARG, "antdt_fill_tables: invalid argument");

@@ -164,6 +164,23 @@ hipError_t launch_dense_adagrad(const DenseAdagradArgs& a, const ShardTab& tab, 
   return hipGetLastError();
 }
 
+// Plain streaming copy, one 16-byte vector per thread: the measured bandwidth that the
+// memory-bound kernels are compared with.
+__global__ __launch_bounds__(256) void stream_copy_kernel(float* __restrict__ dst, const float* __restrict__ src,
+                                                          int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t n4 = n >> 2;
+  if (i < n4) reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+  if (i < (n & 3)) dst[(n4 << 2) + i] = src[(n4 << 2) + i];
+}
+
+hipError_t launch_stream_copy(float* dst, const float* src, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int64_t blocks = ((n >> 2) + 255) / 256 + 1;
+  hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dst, src, n);
+  return hipGetLastError();
+}
+
 hipError_t launch_adam(const AdamArgs& a, hipStream_t s) {
   if (a.n <= 0) return hipSuccess;
   // One 16-byte vector per thread and no grid-stride loop: with 262144 blocks for 2^28 elements

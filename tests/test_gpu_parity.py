@@ -507,6 +507,16 @@ def test_dense_aggregate_adam(n, step, weights):
         assert np.all(np.abs(got - p1) <= bound), "Adam step outside the bound derived from the oracle"
 
 
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 1027, (1 << 20) + 2])
+def test_stream_copy_is_exact(n):
+    import paper_2404_09679_amd as A
+    src = torch.randn(n + 8, device="cuda:0")[4:4 + n].contiguous()   # 16-byte aligned, fresh storage
+    dst = torch.full((n + 4,), 7.0, device="cuda:0")
+    A.stream_copy(dst[:n], src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and bool((dst[n:] == 7.0).all())
+
+
 def test_fill_tables_matches_generator():
     import paper_2404_09679_amd as A
     for dtype, cfg in ((torch.float32, wl.CONFIGS[1]), (torch.bfloat16, wl.scaled(ROW_BF, rows_per_field=3001))):
