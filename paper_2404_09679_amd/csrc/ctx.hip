@@ -34,8 +34,9 @@ int prof_begin(Profiler* p, int kid, hipStream_t s) {
     r.stop = p->pool.back().second;
     p->pool.pop_back();
   } else {
-    if (hipEventCreate(&r.start) != hipSuccess) return -1;
-    if (hipEventCreate(&r.stop) != hipSuccess) return -1;
+    // timing events: no cache write-back at the record (it would disturb what is being timed)
+    if (hipEventCreateWithFlags(&r.start, hipEventDisableSystemFence) != hipSuccess) return -1;
+    if (hipEventCreateWithFlags(&r.stop, hipEventDisableSystemFence) != hipSuccess) return -1;
   }
   (void)hipEventRecord(r.start, s);
   p->recs.push_back(r);
@@ -167,6 +168,12 @@ static int fail(antdt_ctx* c, int code, const std::string& msg) {
     if (e__ != hipSuccess)                                                                 \
       return fail(c, ANTDT_HIP_ERROR, std::string(#expr) + ": " + hipGetErrorString(e__)); \
   } while (0)
+
+// Events that order the library's own streams on one device.  Without the system-scope fence a
+// record does not write the caches back for the host or other devices (work on this device
+// still sees everything the recorded work wrote): on the launch stream that fence costs about
+// 2 us per record and evicts what the next kernel would have found in L2.
+static constexpr unsigned SYNC_EVENT_FLAGS = hipEventDisableTiming | hipEventDisableSystemFence;
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline Profiler* prof_of(antdt_ctx* c) { return c->prof.mode ? &c->prof : nullptr; }
@@ -382,13 +389,13 @@ int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params
   carve(c, (char*)workspace);
   if (!c->side) {
     HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
-    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_fork, SYNC_EVENT_FLAGS));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_join, SYNC_EVENT_FLAGS));
   }
   if (!c->wside) {
     HIP_TRY(c, hipStreamCreateWithFlags(&c->wside, hipStreamNonBlocking));
-    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_wgrad, hipEventDisableTiming));
-    for (int l = 0; l <= c->L; ++l) HIP_TRY(c, hipEventCreateWithFlags(&c->ev_dh[l], hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_wgrad, SYNC_EVENT_FLAGS));
+    for (int l = 0; l <= c->L; ++l) HIP_TRY(c, hipEventCreateWithFlags(&c->ev_dh[l], SYNC_EVENT_FLAGS));
   }
   c->stage = ST_BOUND;
   return refresh_bf16_weights(c, (hipStream_t)stream);
@@ -712,12 +719,10 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
   // gradient of layer l needs dH_{l+1} but nothing needs it before the dense update, so it goes
   // to its own stream and runs beside the rest of the chain and the sparse reduction.
   hipStream_t ws = c->wside ? c->wside : s;
-  if (L > 1 && ws != s) HIP_TRY(c, hipEventRecord(c->ev_dh[L - 1], s));
   ProfScope bwd_scope(c->act_bf16 && L > 1 ? pr : nullptr, KID_GEMM_BWD, s);
   bwd_scope.launches(L - 1);
   Profiler* pr_each = c->act_bf16 ? nullptr : pr;  // the fp32 path has other kernels in between
-  for (int l = L - 2; l >= 0; --l) {
-    if (ws != s) HIP_TRY(c, hipStreamWaitEvent(ws, c->ev_dh[l + 1], 0));
+  auto weight_gradient = [&](int l) -> int {
     if (c->act_bf16) {
       // [dW_l ; db_l][k] = [act_l ; 1]^T dh_{l+1} over the shard's samples: both operands are the
       // transposed copies (sample index contiguous); the ones row yields the bias gradient,
@@ -732,19 +737,26 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
       ProfScope ps(pr, KID_GEMM_WGRAD, ws);
       HIP_TRY(c, launch_gemm(g, tab, ws));
-    } else {
-      {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
-        GemmArgs g;
-        memset(&g, 0, sizeof(g));
-        g.A = act(l); g.lda = ld(l); g.a_kc = 0;
-        g.B = c->dh[l + 1]; g.ldb = c->width[l + 1]; g.b_kc = 0;
-        g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
-        g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
-        g.epi = EPI_PLAIN; g.bf16_in = 0; g.bf16_out = 0;
-        g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
-        ProfScope ps(pr, KID_GEMM_WGRAD, ws);
-        HIP_TRY(c, launch_gemm(g, tab, ws));
-      }
+    } else {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
+      GemmArgs g;
+      memset(&g, 0, sizeof(g));
+      g.A = act(l); g.lda = ld(l); g.a_kc = 0;
+      g.B = c->dh[l + 1]; g.ldb = c->width[l + 1]; g.b_kc = 0;
+      g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
+      g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
+      g.epi = EPI_PLAIN; g.bf16_in = 0; g.bf16_out = 0;
+      g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
+      ProfScope ps(pr, KID_GEMM_WGRAD, ws);
+      HIP_TRY(c, launch_gemm(g, tab, ws));
+    }
+    return ANTDT_OK;
+  };
+  // An event record costs the launch stream about as much as a small kernel, so the weight
+  // gradients are released in pairs: after the data gradient of layer l both dW_l (needs
+  // dH_{l+1}) and dW_{l-1} (needs dH_l) can start.
+  int next_w = L - 2;  // highest layer whose weight gradient is not launched yet
+  for (int l = L - 2; l >= 0; --l) {
+    if (!c->act_bf16) {
       BiasGradArgs b;
       memset(&b, 0, sizeof(b));
       b.dh = c->dh[l + 1]; b.lddh = c->width[l + 1]; b.width = c->width[l + 1]; b.bf16_dh = 0;
@@ -773,7 +785,18 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       ProfScope ps(pr_each, KID_GEMM_DGRAD, s);
       HIP_TRY(c, launch_gemm(g, tab, s));
     }
-    if (l > 0 && ws != s) HIP_TRY(c, hipEventRecord(c->ev_dh[l], s));
+    const bool release = l == 0 || ((L - 2 - l) & 1) == 0;
+    if (release) {
+      if (ws != s) {
+        if (l == 0) bwd_scope.close();
+        HIP_TRY(c, hipEventRecord(c->ev_dh[l], s));
+        HIP_TRY(c, hipStreamWaitEvent(ws, c->ev_dh[l], 0));
+      }
+      for (const int last = l > 0 ? l - 1 : 0; next_w >= last; --next_w) {
+        const int rc = weight_gradient(next_w);
+        if (rc) return rc;
+      }
+    }
   }
   bwd_scope.close();
   if (L > 1 && ws != s) {
@@ -880,7 +903,8 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
   // weight-gradient stream (behind those products, which it needs anyway) beside the sparse
   // update; `s` joins it before this call's work on `s` is complete.
   hipStream_t ds = c->wside ? c->wside : s;
-  if (ds != s) {
+  if (ds != s && c->L == 1) {
+    // (with hidden layers every worker step ends by making this stream wait for the launch stream)
     HIP_TRY(c, hipEventRecord(c->ev_dh[c->L], s));  // everything enqueued on `s` so far (loss, last layer's gradient)
     HIP_TRY(c, hipStreamWaitEvent(ds, c->ev_dh[c->L], 0));
   }
