@@ -30,6 +30,10 @@ WIDE = [wl.RankingConfig("rows-256B", 3, 3000, 64, "f32", "elementwise", 5, (197
                          (41, 23), wl.SEED0 + 206),
         wl.RankingConfig("rows-512B-bf16", 2, 1500, 256, "bf16", "rowwise", 0, (512, 16, 1), "f32", 60, 1.2,
                          (29, 35), wl.SEED0 + 207)]
+# a wide hidden layer: the largest GEMM tile in the forward, data-gradient and grouped
+# weight-gradient products, with a batch that is not a multiple of any tile height
+WIDE_HIDDEN = wl.RankingConfig("wide-hidden-bf16gemm", 4, 20_000, 32, "f32", "elementwise", 5, (133, 4096, 512, 1),
+                               "bf16", 6, 1.1, (700, 37, 0, 863, 1000), wl.SEED0 + 208)
 ONE_LAYER = wl.RankingConfig("single-layer", 3, 1000, 8, "f32", "elementwise", 2, (26, 1), "f32", 5, 1.05,
                              (40, 24), wl.SEED0 + 203, min_bag=0)
 
@@ -436,6 +440,10 @@ def check_against_plain_oracle(cfg):
 def test_mid_bf16_gemm_against_bf16_operand_oracle_and_plain_oracle():
     check_iteration(MID_BF, MID_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True)
     check_against_plain_oracle(MID_BF)
+
+
+def test_wide_hidden_layer_ragged_batch():
+    check_iteration(WIDE_HIDDEN, WIDE_HIDDEN.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True, batched=True)
 
 
 def test_rowwise_state_bf16_tables():
