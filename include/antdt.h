@@ -394,6 +394,15 @@ int antdt_view_coalesced(antdt_ctx* ctx, int32_t f, const int32_t** unique_ids,
  */
 int antdt_profile(antdt_ctx* ctx, int32_t mode, int32_t kernel_id);
 int antdt_profile_read(antdt_ctx* ctx, int32_t kernel_id, int64_t* launches, double* total_ms);
+/*
+ * What a pair of timing events adds to the time it reports: n times on `stream`, a pair with
+ * nothing between its records (mean elapsed time -> *empty_ms) and a pair around the library's
+ * smallest kernel, a two-word store (-> *tiny_ms), each behind such a kernel so that the stream
+ * is busy as it is inside an iteration.  A class duration from antdt_profile_read contains about
+ * *empty_ms per pair of events (at most *tiny_ms, which also holds that kernel's own run time).
+ * Requires antdt_bind; synchronises `stream`; 1 <= n <= 4096.
+ */
+int antdt_profile_overhead(antdt_ctx* ctx, void* stream, int32_t n, double* empty_ms, double* tiny_ms);
 const char* antdt_kernel_name(int32_t kernel_id);
 
 #ifdef __cplusplus

@@ -23,7 +23,7 @@ EXPORTS = [
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
     "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr", "antdt_validate_batch",
-    "antdt_set_shard_scale", "antdt_stream_copy",
+    "antdt_set_shard_scale", "antdt_stream_copy", "antdt_profile_overhead",
     "antdt_dds_create", "antdt_dds_destroy", "antdt_dds_num_shards", "antdt_dds_fetch", "antdt_dds_report_done",
     "antdt_dds_release_worker", "antdt_dds_shard", "antdt_dds_counts", "antdt_simulate_bsp",
 ]
@@ -96,6 +96,7 @@ def _load():
     lib.antdt_set_lr.argtypes = [vp, f32]
     lib.antdt_set_shard_scale.argtypes = [vp, C.POINTER(C.c_double), i32]
     lib.antdt_stream_copy.argtypes = [vp, vp, i64, vp]
+    lib.antdt_profile_overhead.argtypes = [vp, vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.antdt_validate_batch.argtypes = [vp, vp]
     lib.antdt_dds_create.argtypes = [i64, i64, i32, C.POINTER(vp)]
     lib.antdt_dds_destroy.argtypes = [vp]
@@ -302,6 +303,12 @@ class Context:
     # ---------------------------------------------------------- profiling
     def profile(self, mode: int, kernel_id: int = -1):
         self._check(lib.antdt_profile(self._h, mode, kernel_id))
+
+    def profile_overhead(self, n: int = 64) -> Tuple[float, float]:
+        """(empty pair, pair around the smallest kernel): mean elapsed milliseconds."""
+        e, t = C.c_double(), C.c_double()
+        self._check(lib.antdt_profile_overhead(self._h, _stream(), n, C.byref(e), C.byref(t)))
+        return e.value, t.value
 
     def profile_read(self, kernel_id: int) -> Tuple[int, float]:
         n, ms = C.c_int64(), C.c_double()

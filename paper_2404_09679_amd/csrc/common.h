@@ -113,6 +113,7 @@ struct PoolArgs {
 hipError_t launch_pool(const PoolArgs& a, const FieldPtr& fp, hipStream_t s);
 hipError_t launch_validate(const int32_t* ids, const int32_t* offsets, const FieldPtr& fp, int64_t B, int64_t R, int F,
                            int32_t* flags, hipStream_t s);
+hipError_t launch_validate_reset(int32_t* flags, hipStream_t s);
 hipError_t launch_fill_tables(void* tables, int bf16, int F, int64_t R, int D, float scale,
                               hipStream_t s);
 

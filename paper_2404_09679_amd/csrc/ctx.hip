@@ -1077,6 +1077,37 @@ int antdt_profile(antdt_ctx* c, int32_t mode, int32_t kernel_id) {
   return ANTDT_OK;
 }
 
+int antdt_profile_overhead(antdt_ctx* c, void* stream, int32_t n, double* empty_ms, double* tiny_ms) {
+  if (!c || !empty_ms || !tiny_ms || n < 1 || n > 4096)
+    return fail(c, ANTDT_INVALID_ARG, "antdt_profile_overhead: null argument or n outside 1..4096");
+  if (c->stage < ST_BOUND) return fail(c, ANTDT_BAD_STATE, "antdt_profile_overhead: call antdt_bind first");
+  hipStream_t s = (hipStream_t)stream;
+  std::vector<hipEvent_t> ev((size_t)n * 4);
+  for (auto& e : ev) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
+  for (int i = 0; i < n; ++i) {  // the flags kernel is the smallest one the library has
+    HIP_TRY(c, launch_validate_reset(c->vflags, s));
+    HIP_TRY(c, hipEventRecord(ev[4 * i + 0], s));
+    HIP_TRY(c, hipEventRecord(ev[4 * i + 1], s));
+    HIP_TRY(c, launch_validate_reset(c->vflags, s));
+    HIP_TRY(c, hipEventRecord(ev[4 * i + 2], s));
+    HIP_TRY(c, launch_validate_reset(c->vflags, s));
+    HIP_TRY(c, hipEventRecord(ev[4 * i + 3], s));
+  }
+  HIP_TRY(c, hipStreamSynchronize(s));
+  double e_sum = 0.0, t_sum = 0.0;
+  for (int i = 0; i < n; ++i) {
+    float a = 0.f, b = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&a, ev[4 * i + 0], ev[4 * i + 1]));
+    HIP_TRY(c, hipEventElapsedTime(&b, ev[4 * i + 2], ev[4 * i + 3]));
+    e_sum += a;
+    t_sum += b;
+  }
+  for (auto& e : ev) (void)hipEventDestroy(e);
+  *empty_ms = e_sum / n;
+  *tiny_ms = t_sum / n;
+  return ANTDT_OK;
+}
+
 int antdt_profile_read(antdt_ctx* c, int32_t kid, int64_t* launches, double* total_ms) {
   if (!c || !launches || !total_ms) return fail(c, ANTDT_INVALID_ARG, "antdt_profile_read: null argument");
   if (kid < 0 || kid >= KID_COUNT) return fail(c, ANTDT_INVALID_ARG, "antdt_profile_read: kernel id out of range");

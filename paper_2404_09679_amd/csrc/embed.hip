@@ -244,6 +244,11 @@ __global__ void validate_reset_kernel(int32_t* flags) {
   }
 }
 
+hipError_t launch_validate_reset(int32_t* flags, hipStream_t s) {
+  hipLaunchKernelGGL(validate_reset_kernel, dim3(1), dim3(64), 0, s, flags);
+  return hipGetLastError();
+}
+
 hipError_t launch_validate(const int32_t* ids, const int32_t* offsets, const FieldPtr& fp, int64_t B, int64_t R, int F,
                            int32_t* flags, hipStream_t s) {
   hipLaunchKernelGGL(validate_reset_kernel, dim3(1), dim3(64), 0, s, flags);

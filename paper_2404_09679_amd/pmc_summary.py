@@ -5,6 +5,9 @@
 <dir> holds four rocprofv3 --pmc outputs (csv), one counter each:
     bench_FETCH_SIZE/ bench_WRITE_SIZE/   python3 bench.py --steps 40 --warmup 10 --no-cpu-baseline
     copy_FETCH_SIZE/  copy_WRITE_SIZE/    python3 bench.py --workload copy-calibration --steps 10
+and optionally bench_MFMA/ (--pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE,
+the same bench command): matrix-core busy cycles of the matrix products against the cycles
+the device was active during them.
 The counters are in KiB per dispatch.  They are scaled by what the same counter reads for the
 plain copy kernel (1 GiB read and 1 GiB written per launch): on this machine FETCH_SIZE reads
 half the bytes actually fetched.  Dispatches are walked in order; a step starts at the pooling
@@ -18,9 +21,9 @@ import glob
 import sys
 
 
-def _rows(d):
+def _rows(d, counter=None):
     path = glob.glob(f"{d}/**/*counter_collection.csv", recursive=True)[0]
-    rows = list(csv.DictReader(open(path)))
+    rows = [r for r in csv.DictReader(open(path)) if counter is None or r["Counter_Name"] == counter]
     rows.sort(key=lambda r: int(r["Dispatch_Id"]))
     return rows
 
@@ -70,6 +73,27 @@ def main(d):
     for c in sorted(f):
         fm, wm = f[c] * fscale * 1024 / 1e6, w.get(c, 0.0) * wscale * 1024 / 1e6
         print(f"{c:18s} {fm:11.1f} {wm:11.1f} {fm + wm:10.1f}")
+
+
+    if glob.glob(f"{d}/bench_MFMA"):
+        mfma_summary(f"{d}/bench_MFMA")
+
+
+def mfma_summary(d, simds=1024, xcds=8):
+    """Matrix-core utilisation of the matrix-product classes: busy cycles summed over the SIMDs,
+    divided by (cycles the device was active in those dispatches x number of SIMDs); and the
+    flops the counters saw (512 per counted operation).  The active-cycle counter is reported
+    summed over the device's XCDs (one instance each), so it is divided by their number."""
+    busy = class_totals(_rows(d, "SQ_VALU_MFMA_BUSY_CYCLES"))
+    mops = class_totals(_rows(d, "SQ_INSTS_VALU_MFMA_MOPS_BF16"))
+    act = class_totals(_rows(d, "GRBM_GUI_ACTIVE"))
+    print(f"{'class':18s} {'MFMA busy cycles':>17s} {'active cycles':>14s} {'utilisation':>12s} {'GFLOP counted':>14s}   per step")
+    for c in sorted(busy):
+        if not c.startswith("gemm"):
+            continue
+        active = act.get(c, 0.0) / xcds
+        util = busy[c] / max(active * simds, 1.0)
+        print(f"{c:18s} {busy[c]:17.0f} {active:14.0f} {100 * util:11.1f}% {mops.get(c, 0.0) * 512 / 1e9:14.2f}")
 
 
 if __name__ == "__main__":
