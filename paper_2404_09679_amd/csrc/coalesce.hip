@@ -5,6 +5,8 @@
 //   G[u, :] = sum over the run of w(sample) * dX[sample, field slice].
 // No floating-point atomics are used, so the sums are bitwise repeatable.  The reduction can
 // apply the row-sparse Adagrad step of each row at once (the parameter update of Section II).
+#include <algorithm>
+
 #include "common.h"
 
 namespace antdt {
@@ -324,6 +326,73 @@ __global__ __launch_bounds__(SORT_THREADS) void seg_emit_kernel(SegArgs a, Field
     }
 }
 
+// Runs longer than the threshold are cut into chunks of `chunk` lookups; the list of such runs
+// and the list of their chunks are built here, beside the run table, so that the reduction
+// kernel finds them ready.  The order of the lists is arbitrary (it does not affect any sum:
+// a run's chunk sums are added in chunk order).
+constexpr int QUEUE_RUNS = 8;  // runs per thread
+__global__ __launch_bounds__(256) void seg_queue_kernel(SegArgs a) {
+  __shared__ int wl[4], wc[4], base[2];
+  const int U = a.ubase[a.F];
+  if ((int64_t)blockIdx.x * 256 * QUEUE_RUNS >= U) return;
+  const int64_t u0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * QUEUE_RUNS;
+  // One position in the two lists per block (a returning atomic on one address takes the
+  // memory system some ten nanoseconds: one per long run would make this the longest kernel
+  // of the structure), the places inside the block's share by a prefix sum.
+  int len[QUEUE_RUNS], nl = 0, nc = 0;
+#pragma unroll
+  for (int i = 0; i < QUEUE_RUNS; ++i) {
+    const int64_t u = u0 + i;
+    len[i] = u < U ? a.segabs[u + 1] - a.segabs[u] : 0;
+    if (len[i] > a.long_threshold) {
+      ++nl;
+      nc += (len[i] + a.chunk - 1) / a.chunk;
+    }
+  }
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int il = nl, ic = nc;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int vl = __shfl_up(il, o, 64), vc = __shfl_up(ic, o, 64);
+    if (lane >= o) {
+      il += vl;
+      ic += vc;
+    }
+  }
+  if (lane == 63) {
+    wl[w] = il;
+    wc[w] = ic;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int tl = (wl[0] + wl[1]) + (wl[2] + wl[3]), tc = (wc[0] + wc[1]) + (wc[2] + wc[3]);
+    base[0] = tl ? atomicAdd(&a.counters[0], tl) : 0;
+    base[1] = tc ? atomicAdd(&a.counters[1], tc) : 0;
+  }
+  __syncthreads();
+  int slot = base[0] + il - nl, item = base[1] + ic - nc;
+  for (int i = 0; i < w; ++i) {
+    slot += wl[i];
+    item += wc[i];
+  }
+#pragma unroll
+  for (int i = 0; i < QUEUE_RUNS; ++i) {
+    if (len[i] <= a.long_threshold) continue;
+    const int nch = (len[i] + a.chunk - 1) / a.chunk;
+    if (slot < a.long_cap && item + nch <= a.item_cap) {  // (the capacities are upper bounds: always true)
+      a.long_seg[slot * 3 + 0] = (int)(u0 + i);
+      a.long_seg[slot * 3 + 1] = item;
+      a.long_seg[slot * 3 + 2] = nch;
+      for (int q = 0; q < nch; ++q) {
+        a.items[(item + q) * 2 + 0] = (int)(u0 + i);
+        a.items[(item + q) * 2 + 1] = q;
+      }
+    }
+    ++slot;
+    item += nch;
+  }
+}
+
 // ------------------------------------------------- weighted run sums (+ update)
 struct Row4 {
   float v[4];
@@ -425,58 +494,16 @@ __device__ __forceinline__ void load_row(const SegArgs& a, int64_t row, int c, f
   else s0 = *reinterpret_cast<const float4*>(a.state + row * a.D + c * 4);
 }
 
-// One group of D/4 lanes per run.  Short runs are summed in sorted (= sample) order and, when
-// `UPDATE`, the Adagrad step of the row is applied at once (the coalesced gradient never
-// goes to memory); otherwise the sum is written to G.  Runs longer than the threshold are
-// cut into chunks that are queued for the block kernel below.
-template <typename TT, bool ROWWISE, bool UPDATE, bool MEAN>
-__global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a) {
-  const int lps = a.D >> 2;
-  const int U = a.ubase[a.F];
-  const int groups_per_block = 256 / lps;
-  const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
-  for (int64_t u = (int64_t)blockIdx.x * groups_per_block + g; u < U; u += (int64_t)gridDim.x * groups_per_block) {
-    const int b = a.segabs[u], e = a.segabs[u + 1];
-    const int f = a.ufield[u];
-    const int64_t row = (int64_t)f * a.R + min(max(a.uniq[u], 0), (int)(a.R - 1));
-    if (e - b > a.long_threshold) {
-      if (c == 0) {
-        const int nch = (e - b + a.chunk - 1) / a.chunk;
-        const int slot = atomicAdd(&a.counters[0], 1);
-        const int base = atomicAdd(&a.counters[1], nch);
-        if (slot < a.long_cap && base + nch <= a.item_cap) {
-          a.long_seg[slot * 3 + 0] = (int)u;
-          a.long_seg[slot * 3 + 1] = base;
-          a.long_seg[slot * 3 + 2] = nch;
-          for (int q = 0; q < nch; ++q) {
-            a.items[(base + q) * 2 + 0] = (int)u;
-            a.items[(base + q) * 2 + 1] = q;
-          }
-        }
-      }
-      continue;
-    }
-    float p0[4] = {0.f, 0.f, 0.f, 0.f};
-    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f);
-    float srow0 = 0.f;
-    if (UPDATE) load_row<TT, ROWWISE>(a, row, c, p0, s0, srow0);
-    Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
-    accumulate_run<MEAN>(a, f, c, b, e, 1, gsum);
-    if (UPDATE) adagrad_row<TT, ROWWISE>(a, row, c, lps, gsum, p0, s0, srow0);
-    else *reinterpret_cast<float4*>(a.G + u * a.D + c * 4) = make_float4(gsum.v[0], gsum.v[1], gsum.v[2], gsum.v[3]);
-  }
-}
-
-// One block per chunk of a long run: the lane groups stride over the chunk, then their
-// partial sums are added in group order (fixed order: repeatable bit for bit).
+// Chunk sums of the long runs.  One block per chunk: the lane groups stride over the chunk, then
+// their partial sums are added in group order (fixed order: repeatable bit for bit).
 template <bool MEAN>
-__global__ __launch_bounds__(256) void seg_chunk_kernel(SegArgs a) {
+__device__ __forceinline__ void chunk_sums(const SegArgs& a, int first, int step) {
   __shared__ float4 red[256];
   const int lps = a.D >> 2;
   const int ngroups = 256 / lps;
   const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
   const int count = min(a.counters[1], a.item_cap);
-  for (int idx = blockIdx.x; idx < count; idx += gridDim.x) {
+  for (int idx = first; idx < count; idx += step) {
     const int u = a.items[idx * 2], q = a.items[idx * 2 + 1];
     const int b = a.segabs[u] + q * a.chunk, e = min(a.segabs[u + 1], b + a.chunk);
     const int f = a.ufield[u];
@@ -495,6 +522,37 @@ __global__ __launch_bounds__(256) void seg_chunk_kernel(SegArgs a) {
     }
     if (g == 0) *reinterpret_cast<float4*>(a.partial + (int64_t)idx * a.D + c * 4) = red[c];
     __syncthreads();
+  }
+}
+
+// The first `chunk_blocks` blocks take the chunks of the long runs (their sums are added up by
+// the kernel after this one); the others work one group of D/4 lanes per run: short runs are
+// summed in sorted (= sample) order and, when `UPDATE`, the Adagrad step of the row is applied
+// at once (the coalesced gradient never goes to memory); otherwise the sum is written to G.
+template <typename TT, bool ROWWISE, bool UPDATE, bool MEAN>
+__global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a, int chunk_blocks) {
+  if ((int)blockIdx.x < chunk_blocks) {
+    chunk_sums<MEAN>(a, blockIdx.x, chunk_blocks);
+    return;
+  }
+  const int64_t bid = (int64_t)blockIdx.x - chunk_blocks, nblk = (int64_t)gridDim.x - chunk_blocks;
+  const int lps = a.D >> 2;
+  const int U = a.ubase[a.F];
+  const int groups_per_block = 256 / lps;
+  const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
+  for (int64_t u = bid * groups_per_block + g; u < U; u += nblk * groups_per_block) {
+    const int b = a.segabs[u], e = a.segabs[u + 1];
+    if (e - b > a.long_threshold) continue;
+    const int f = a.ufield[u];
+    const int64_t row = (int64_t)f * a.R + min(max(a.uniq[u], 0), (int)(a.R - 1));
+    float p0[4] = {0.f, 0.f, 0.f, 0.f};
+    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float srow0 = 0.f;
+    if (UPDATE) load_row<TT, ROWWISE>(a, row, c, p0, s0, srow0);
+    Row4 gsum = {{0.f, 0.f, 0.f, 0.f}};
+    accumulate_run<MEAN>(a, f, c, b, e, 1, gsum);
+    if (UPDATE) adagrad_row<TT, ROWWISE>(a, row, c, lps, gsum, p0, s0, srow0);
+    else *reinterpret_cast<float4*>(a.G + u * a.D + c * 4) = make_float4(gsum.v[0], gsum.v[1], gsum.v[2], gsum.v[3]);
   }
 }
 
@@ -538,11 +596,12 @@ template <typename TT, bool ROWWISE, bool UPDATE, bool MEAN>
 void launch_reduce_pooling(const SegArgs& a, unsigned blocks, Profiler* prof, hipStream_t s) {
   {
     ProfScope ps(prof, UPDATE ? KID_SPARSE_ADAGRAD : KID_SEG_REDUCE, s);
-    hipLaunchKernelGGL((seg_reduce_kernel<TT, ROWWISE, UPDATE, MEAN>), dim3(blocks), dim3(256), 0, s, a);
+    constexpr int CHUNK_BLOCKS = 2048;
+    hipLaunchKernelGGL((seg_reduce_kernel<TT, ROWWISE, UPDATE, MEAN>), dim3(blocks + CHUNK_BLOCKS), dim3(256), 0, s, a,
+                       CHUNK_BLOCKS);
   }
   {
     ProfScope ps(prof, KID_SEG_REDUCE_LONG, s);
-    hipLaunchKernelGGL(seg_chunk_kernel<MEAN>, dim3(2048), dim3(256), 0, s, a);
     hipLaunchKernelGGL((seg_finish_kernel<TT, ROWWISE, UPDATE>), dim3(64), dim3(256), 0, s, a);
   }
 }
@@ -592,6 +651,9 @@ hipError_t launch_segments(const SegArgs& a, const FieldPtr& fp, const TileBase&
   if (a.total_tiles > 0) {
     ProfScope ps(prof, KID_SEG_EMIT, s);
     hipLaunchKernelGGL(seg_emit_kernel, grid, dim3(SORT_THREADS), 0, s, a, fp, tb);
+    const int64_t nnz = fp.p[a.F];
+    const unsigned qb = (unsigned)((nnz + 256 * QUEUE_RUNS - 1) / (256 * QUEUE_RUNS));  // runs <= lookups
+    hipLaunchKernelGGL(seg_queue_kernel, dim3(qb), dim3(256), 0, s, a);
   }
   return hipGetLastError();
 }
@@ -602,15 +664,6 @@ hipError_t launch_mask_pack(const int32_t* ids, const int32_t* lookup_sample, co
   hipLaunchKernelGGL(mask_count_kernel, dim3(1), dim3(256), 0, s, offsets, B, F, tab, cbase);
   hipLaunchKernelGGL(mask_pack_kernel, dim3(tab.K, F), dim3(256), 0, s, ids, lookup_sample, offsets, B, fp, tab, cbase,
                      ids_out, pay_out);
-  return hipGetLastError();
-}
-
-__global__ void zero_counters_kernel(int32_t* c) {
-  if (threadIdx.x < 2) c[threadIdx.x] = 0;
-}
-
-hipError_t launch_zero_counters(int32_t* counters, hipStream_t s) {
-  hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, counters);
   return hipGetLastError();
 }
 

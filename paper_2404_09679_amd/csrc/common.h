@@ -262,7 +262,6 @@ hipError_t launch_mask_pack(const int32_t* ids, const int32_t* lookup_sample, co
                             const FieldPtr& fp, const ShardTab& tab, int64_t* cbase, int32_t* ids_out,
                             int32_t* pay_out, hipStream_t s);
 hipError_t launch_seg_reduce(const SegArgs& a, int64_t nnz_total, Profiler* prof, hipStream_t s);
-hipError_t launch_zero_counters(int32_t* counters, hipStream_t s);
 
 // ---------------------------------------------------------------- optim.hip
 struct DenseAggArgs {

@@ -546,12 +546,6 @@ static void fill_seg_args(antdt_ctx* c, SegArgs& a) {
   a.table_bf16 = m.table_dtype == ANTDT_BF16; a.rowwise = m.adagrad_state == ANTDT_STATE_ROWWISE;
 }
 
-// Resets the long-run queues (the reduction kernels fill them again).
-static int reset_queues(antdt_ctx* c, hipStream_t s) {
-  HIP_TRY(c, launch_zero_counters(c->counters, s));
-  return ANTDT_OK;
-}
-
 static void set_weights(antdt_ctx* c) {
   const int K = c->tab.K;
   int64_t tot = 0;
@@ -912,10 +906,6 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
     SegArgs a;
     fill_seg_args(c, a);
     a.update = 1;
-    if (c->g_valid) {  // a view ran the reduction already and filled the queues
-      const int rc = reset_queues(c, s);
-      if (rc) return rc;
-    }
     HIP_TRY(c, launch_seg_reduce(a, c->afp.p[m.num_fields], pr, s));
   }
   {
