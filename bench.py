@@ -31,12 +31,12 @@ MEASURED_TRAFFIC = {
     "cfg2": {
         "gemm_fwd": (73.7e6, "gemm.hip"), "gemm_bwd": (90.6e6, "gemm.hip"), "gemm_wgrad": (192.8e6, "gemm.hip"),
         "pool": (92.3e6, "embed.hip"),
-        "sparse_adagrad": (226.5e6, "coalesce.hip"), "seg_reduce_long": (47.8e6, "coalesce.hip"),
+        "sparse_adagrad": (272.0e6, "coalesce.hip"), "seg_reduce_long": (1.5e6, "coalesce.hip"),
         "dense_adagrad": (100.7e6, "optim.hip"),
     },
     "sha1": {"gemm.hip": "02854f0be5c6131691816f640c656ece33427420",
              "embed.hip": "e8c218459c0d05e5dad1b82f3825f9b54cbda8df",
-             "coalesce.hip": "ea520d568959b4983df6e70aa3d025b64cf4326d",
+             "coalesce.hip": "6cf580008c765311d078ac682a81ea9f007430e2",
              "optim.hip": "398ec0d942ea14234c551490884f94a81795ca87"},
 }
 
