@@ -34,7 +34,7 @@ MEASURED_TRAFFIC = {
         "sparse_adagrad": (272.0e6, "coalesce.hip"), "seg_reduce_long": (1.5e6, "coalesce.hip"),
         "dense_adagrad": (100.7e6, "optim.hip"),
     },
-    "sha1": {"gemm.hip": "02854f0be5c6131691816f640c656ece33427420",
+    "sha1": {"gemm.hip": "763734d5619304d69994a48d5d079a2878a9b88d",
              "embed.hip": "e8c218459c0d05e5dad1b82f3825f9b54cbda8df",
              "coalesce.hip": "6cf580008c765311d078ac682a81ea9f007430e2",
              "optim.hip": "398ec0d942ea14234c551490884f94a81795ca87"},

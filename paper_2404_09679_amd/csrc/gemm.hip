@@ -49,13 +49,15 @@ __device__ __forceinline__ uint32_t relu_mask2(uint32_t v, uint32_t mk) {
 }
 
 // C[m, n] = sum_{k in [ks, ke)} A[m*lda + k] * B[n*ldb + k].
-// Block tile (64*TM) x (64*TN), four wavefronts 2x2, each TM x TN MFMA tiles of 32x32.
+// Block tile (32*TM*WR) x (32*TN*WC): WR x WC wavefronts, each TM x TN MFMA tiles of 32x32.
 // Global -> registers -> LDS with the next tile's loads in flight during the MFMAs.
 // Blocks are numbered so that the blocks sharing an A row-panel run on the same XCD (L2).
-template <int TM, int TN, bool GROUPED>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab, int tiles_m, int tiles_n) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;
-  constexpr int VA = BM * BK / 8 / 256, VB = BN * BK / 8 / 256;  // 16-byte vectors per thread
+template <int TM, int TN, int WR, int WC, bool GROUPED>
+__global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, ShardTab tab, int tiles_m, int tiles_n) {
+  constexpr int THREADS = 64 * WR * WC;
+  constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
+  constexpr int VA = BM * BK / 8 / THREADS, VB = BN * BK / 8 / THREADS;  // 16-byte vectors per thread
+  static_assert(VA >= 1 && VB >= 1 && VA * THREADS * 8 == BM * BK && VB * THREADS * 8 == BN * BK, "tile / thread count");
   __shared__ __attribute__((aligned(16))) bf16_t lds[(BM + BN) * PITCH];
   bf16_t* la = lds;
   bf16_t* lb = lds + BM * PITCH;
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
   const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 1, wc = wave & 1;
+  const int wr = wave / WC, wc = wave % WC;
   const int fr = lane & 31, fg = lane >> 5;
 
   // Two register stages: while tile kt is multiplied out of LDS, tiles kt+1 and kt+2 are in
@@ -90,13 +92,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
   auto load_tile = [&](int kt, uint4 (&ra)[VA], uint4 (&rb)[VB]) {
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
-      const int v = tid + i * 256;
+      const int v = tid + i * THREADS;
       const int row = min(m0 + (v >> 3), p.M - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
       ra[i] = *reinterpret_cast<const uint4*>(A + (int64_t)row * p.lda + k);
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
-      const int v = tid + i * 256;
+      const int v = tid + i * THREADS;
       const int row = min(n0 + (v >> 3), p.N - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
       rb[i] = *reinterpret_cast<const uint4*>(B + (int64_t)row * p.ldb + k);
     }
@@ -110,13 +112,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
   auto store_tile = [&](int kt, const uint4 (&ra)[VA], const uint4 (&rb)[VB]) {
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
-      const int v = tid + i * 256;
+      const int v = tid + i * THREADS;
       const uint4 val = fix(ra[i], m0 + (v >> 3) < p.M, kfirst + kt * BK + (v & 7) * 8);
       *reinterpret_cast<uint4*>(la + (v >> 3) * PITCH + (v & 7) * 8) = val;
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
-      const int v = tid + i * 256;
+      const int v = tid + i * THREADS;
       const uint4 val = fix(rb[i], n0 + (v >> 3) < p.N, kfirst + kt * BK + (v & 7) * 8);
       *reinterpret_cast<uint4*>(lb + (v >> 3) * PITCH + (v & 7) * 8) = val;
     }
@@ -137,10 +139,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
       bf16x8 af[TM], bfr[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(la + (wr * (BM / 2) + i * 32 + fr) * PITCH + kk + fg * 8);
+        af[i] = *reinterpret_cast<const bf16x8*>(la + (wr * (32 * TM) + i * 32 + fr) * PITCH + kk + fg * 8);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(lb + (wc * (BN / 2) + j * 32 + fr) * PITCH + kk + fg * 8);
+        bfr[j] = *reinterpret_cast<const bf16x8*>(lb + (wc * (32 * TN) + j * 32 + fr) * PITCH + kk + fg * 8);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -177,69 +179,81 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
   constexpr int WM = 32 * TM, WN = 32 * TN;
   const int mw = m0 + wr * WM, nw = n0 + wc * WN;
   if (p.bf16_out) {
+    // staged PTM tile rows at a time: the largest number whose slices (one per wavefront) fit the
+    // operand buffer
     constexpr int SP = WN + 8;
-    bf16_t* st = lds + wave * (WM * SP);
+    constexpr int CAP = (BM + BN) * PITCH / (WR * WC * 32 * SP);
+    static_assert(CAP >= 1, "epilogue staging exceeds the operand buffer");
+    constexpr int PTM = CAP < TM ? (TM % CAP == 0 ? CAP : 1) : TM, PM = 32 * PTM;
+    bf16_t* st = lds + wave * (PM * SP);
     float bias[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int n = nw + j * 32 + fr;
       bias[j] = (p.epi == EPI_BIAS_RELU && n < p.N) ? p.bias[n] : 0.0f;
     }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float v = acc[i][j][e];
-          if (p.epi == EPI_BIAS_RELU) v = fmaxf(v + bias[j], 0.0f);
-          st[(i * 32 + 8 * (e >> 2) + 4 * fg + (e & 3)) * SP + j * 32 + fr] = f2bf(v);
-        }
-    __syncthreads();
     constexpr int CPR = WN / 8;    // 16-byte pieces per row
     constexpr int RPI = 64 / CPR;  // rows per wavefront instruction
     const int rr = lane / CPR, cc = (lane % CPR) * 8;
     bf16_t* Cb = reinterpret_cast<bf16_t*>(C);
 #pragma unroll
-    for (int r0 = 0; r0 < WM; r0 += RPI) {
-      const int r = r0 + rr, m = mw + r, n = nw + cc;
-      if (m < p.M && n < p.N) {
-        uint4 val = *reinterpret_cast<const uint4*>(st + r * SP + cc);
-        if (p.epi == EPI_RELU_MASK) {
-          const uint4 mk = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.mask) + (int64_t)m * p.ldmask + n);
-          val = make_uint4(relu_mask2(val.x, mk.x), relu_mask2(val.y, mk.y), relu_mask2(val.z, mk.z), relu_mask2(val.w, mk.w));
-          if (p.CT) *reinterpret_cast<uint4*>(st + r * SP + cc) = val;
-        }
-        *reinterpret_cast<uint4*>(Cb + (int64_t)m * p.ldc + n) = val;
-      }
-    }
-    if (p.CT) {
+    for (int ip = 0; ip < TM; ip += PTM) {
+      if (ip) __syncthreads();
+#pragma unroll
+      for (int i = 0; i < PTM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            float v = acc[ip + i][j][e];
+            if (p.epi == EPI_BIAS_RELU) v = fmaxf(v + bias[j], 0.0f);
+            st[(i * 32 + 8 * (e >> 2) + 4 * fg + (e & 3)) * SP + j * 32 + fr] = f2bf(v);
+          }
       __syncthreads();
-      constexpr int CPI = WN < 64 ? WN : 64;  // columns per wavefront instruction
-      constexpr int HV = 64 / CPI;
-      const int col = lane % CPI, hv = lane / CPI;
-      const int n = nw + col;
-      for (int mc = hv; mc < WM / 8; mc += HV) {
-        const int mb = mw + mc * 8;
-        if (n < p.N && mb < p.M) {
-          bf16_t h[8];
+      const int mp = mw + ip * 32;  // first row of this pass
 #pragma unroll
-          for (int e = 0; e < 8; ++e) h[e] = st[(mc * 8 + e) * SP + col];
-          bf16_t* dst = p.CT + (int64_t)n * p.ldct + p.ct_col0 + mb;
-          if (mb + 7 < p.M && ((p.ct_col0 + mb) & 7) == 0) {
-            *reinterpret_cast<uint4*>(dst) = make_uint4((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16),
-                                                        (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16));
-          } else {
+      for (int r0 = 0; r0 < PM; r0 += RPI) {
+        const int r = r0 + rr, m = mp + r, n = nw + cc;
+        if (m < p.M && n < p.N) {
+          uint4 val = *reinterpret_cast<const uint4*>(st + r * SP + cc);
+          if (p.epi == EPI_RELU_MASK) {
+            const uint4 mk = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.mask) + (int64_t)m * p.ldmask + n);
+            val = make_uint4(relu_mask2(val.x, mk.x), relu_mask2(val.y, mk.y), relu_mask2(val.z, mk.z), relu_mask2(val.w, mk.w));
+            if (p.CT) *reinterpret_cast<uint4*>(st + r * SP + cc) = val;
+          }
+          *reinterpret_cast<uint4*>(Cb + (int64_t)m * p.ldc + n) = val;
+        }
+      }
+      if (p.CT) {
+        __syncthreads();
+        constexpr int CPI = WN < 64 ? WN : 64;  // columns per wavefront instruction
+        constexpr int HV = 64 / CPI;
+        const int col = lane % CPI, hv = lane / CPI;
+        const int n = nw + col;
+        for (int mc = hv; mc < PM / 8; mc += HV) {
+          const int mb = mp + mc * 8;
+          if (n < p.N && mb < p.M) {
+            bf16_t h[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (mb + e < p.M) dst[e] = h[e];
+            for (int e = 0; e < 8; ++e) h[e] = st[(mc * 8 + e) * SP + col];
+            bf16_t* dst = p.CT + (int64_t)n * p.ldct + p.ct_col0 + mb;
+            if (mb + 7 < p.M && ((p.ct_col0 + mb) & 7) == 0) {
+              *reinterpret_cast<uint4*>(dst) = make_uint4((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16),
+                                                          (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16));
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (mb + e < p.M) dst[e] = h[e];
+            }
           }
         }
       }
     }
   } else {
     constexpr int SPF = WN + 4;
-    constexpr int ROWS = 32;  // rows staged per pass: one MFMA tile row
+    // rows staged per pass: one MFMA tile row, or half of one where eight wavefronts share the buffer
+    constexpr int ROWS = (WR * WC * 32 * SPF * 4 <= (BM + BN) * PITCH * 2) ? 32 : 16;
+    static_assert(WR * WC * ROWS * SPF * 4 <= (BM + BN) * PITCH * 2, "epilogue staging exceeds the operand buffer");
     float* stf = reinterpret_cast<float*>(lds) + wave * (ROWS * SPF);
     constexpr int CPR = WN / 4;
     constexpr int RPI = 64 / CPR;
@@ -248,11 +262,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, ShardTab tab
 #pragma unroll
     for (int pass = 0; pass < WM / ROWS; ++pass) {
       if (pass) __syncthreads();
+      // a D fragment's element e sits in row 8*(e/4) + 4*fg + e%4 of its 32-row tile: elements
+      // 0..7 are the upper 16 rows, 8..15 the lower
+      constexpr int EPP = ROWS / 2;               // fragment elements per pass
+      const int tile = pass * ROWS / 32, e0 = (pass * ROWS % 32) / 2;
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          stf[(8 * (e >> 2) + 4 * fg + (e & 3)) * SPF + j * 32 + fr] = acc[pass][j][e];
+        for (int e = 0; e < EPP; ++e)
+          stf[(8 * (e >> 2) + 4 * fg + (e & 3)) * SPF + j * 32 + fr] = acc[tile][j][e0 + e];
       __syncthreads();
 #pragma unroll
       for (int r0 = 0; r0 < ROWS; r0 += RPI) {
@@ -361,12 +379,13 @@ __global__ __launch_bounds__(256) void ones_row_kernel(OnesRowArgs a) {
   for (int r = 1; r <= a.zero_rows; ++r) a.base[(int64_t)(a.row + r) * a.ld + i] = 0;
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int WR, int WC>
 void launch_bf16_variant(const GemmArgs& a, const ShardTab& tab, int groups, hipStream_t s) {
-  const int tiles_m = (a.M + 64 * TM - 1) / (64 * TM), tiles_n = (a.N + 64 * TN - 1) / (64 * TN);
-  dim3 grid(tiles_m * tiles_n, 1, groups);
-  if (a.grouped) hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, true>), grid, dim3(256), 0, s, a, tab, tiles_m, tiles_n);
-  else hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, false>), grid, dim3(256), 0, s, a, tab, tiles_m, tiles_n);
+  constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  dim3 grid(tiles_m * tiles_n, 1, groups), block(64 * WR * WC);
+  if (a.grouped) hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, WR, WC, true>), grid, block, 0, s, a, tab, tiles_m, tiles_n);
+  else hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, WR, WC, false>), grid, block, 0, s, a, tab, tiles_m, tiles_n);
 }
 
 }  // namespace
@@ -387,9 +406,14 @@ hipError_t launch_gemm(const GemmArgs& a, const ShardTab& tab, hipStream_t s) {
   // epilogue: measured 294 against 305 us per step with the threshold at 300 instead of 200.
   constexpr int64_t MIN_BLOCKS = 300;
   auto blocks = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * groups; };
-  if (blocks(128, 128) >= MIN_BLOCKS) launch_bf16_variant<2, 2>(a, tab, groups, s);
-  else if (blocks(128, 64) >= MIN_BLOCKS) launch_bf16_variant<2, 1>(a, tab, groups, s);
-  else launch_bf16_variant<1, 1>(a, tab, groups, s);
+  // Eight wavefronts on a 256 x 128 tile (a quarter fewer operand bytes per compute unit than
+  // 128 x 128) pay off only where there are blocks enough that the last, partly filled round
+  // of blocks does not matter: measured -5 % on a step whose products have thousands of
+  // blocks, +1 % where they have about five hundred.
+  if (blocks(256, 128) >= 4 * 256) launch_bf16_variant<2, 2, 4, 2>(a, tab, groups, s);
+  else if (blocks(128, 128) >= MIN_BLOCKS) launch_bf16_variant<2, 2, 2, 2>(a, tab, groups, s);
+  else if (blocks(128, 64) >= MIN_BLOCKS) launch_bf16_variant<2, 1, 2, 2>(a, tab, groups, s);
+  else launch_bf16_variant<1, 1, 2, 2>(a, tab, groups, s);
   return hipGetLastError();
 }
 

@@ -30,10 +30,13 @@ WIDE = [wl.RankingConfig("rows-256B", 3, 3000, 64, "f32", "elementwise", 5, (197
                          (41, 23), wl.SEED0 + 206),
         wl.RankingConfig("rows-512B-bf16", 2, 1500, 256, "bf16", "rowwise", 0, (512, 16, 1), "f32", 60, 1.2,
                          (29, 35), wl.SEED0 + 207)]
-# a wide hidden layer: the largest GEMM tile in the forward, data-gradient and grouped
-# weight-gradient products, with a batch that is not a multiple of any tile height
+# a wide hidden layer and a batch of 8232 samples in 16 uneven shards: every matrix product of the
+# step (forward and data gradient with bf16 results, grouped weight gradients with fp32 results)
+# has more than a thousand 256 x 128 tiles, the shape the eight-wavefront kernel is chosen for,
+# and the batch is not a multiple of any tile height
 WIDE_HIDDEN = wl.RankingConfig("wide-hidden-bf16gemm", 4, 20_000, 32, "f32", "elementwise", 5, (133, 4096, 512, 1),
-                               "bf16", 6, 1.1, (700, 37, 0, 863, 1000), wl.SEED0 + 208)
+                               "bf16", 6, 1.1, (700, 37, 0, 863, 1000, 512, 640, 511, 513, 300, 1, 999, 256, 400, 500, 1000),
+                               wl.SEED0 + 208)
 ONE_LAYER = wl.RankingConfig("single-layer", 3, 1000, 8, "f32", "elementwise", 2, (26, 1), "f32", 5, 1.05,
                              (40, 24), wl.SEED0 + 203, min_bag=0)
 
