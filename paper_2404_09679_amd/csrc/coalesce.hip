@@ -593,7 +593,7 @@ __global__ __launch_bounds__(256) void seg_finish_kernel(SegArgs a) {
 }
 
 template <typename TT, bool ROWWISE, bool UPDATE, bool MEAN>
-void launch_reduce_pooling(const SegArgs& a, unsigned blocks, Profiler* prof, hipStream_t s) {
+void launch_reduce_pooling(const SegArgs& a, unsigned blocks, unsigned finish_blocks, Profiler* prof, hipStream_t s) {
   {
     ProfScope ps(prof, UPDATE ? KID_SPARSE_ADAGRAD : KID_SEG_REDUCE, s);
     constexpr int CHUNK_BLOCKS = 2048;
@@ -602,14 +602,14 @@ void launch_reduce_pooling(const SegArgs& a, unsigned blocks, Profiler* prof, hi
   }
   {
     ProfScope ps(prof, KID_SEG_REDUCE_LONG, s);
-    hipLaunchKernelGGL((seg_finish_kernel<TT, ROWWISE, UPDATE>), dim3(64), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((seg_finish_kernel<TT, ROWWISE, UPDATE>), dim3(finish_blocks), dim3(256), 0, s, a);
   }
 }
 
 template <typename TT, bool ROWWISE, bool UPDATE>
-void launch_reduce_variant(const SegArgs& a, unsigned blocks, Profiler* prof, hipStream_t s) {
-  if (a.mean_pool) launch_reduce_pooling<TT, ROWWISE, UPDATE, true>(a, blocks, prof, s);
-  else launch_reduce_pooling<TT, ROWWISE, UPDATE, false>(a, blocks, prof, s);
+void launch_reduce_variant(const SegArgs& a, unsigned blocks, unsigned finish_blocks, Profiler* prof, hipStream_t s) {
+  if (a.mean_pool) launch_reduce_pooling<TT, ROWWISE, UPDATE, true>(a, blocks, finish_blocks, prof, s);
+  else launch_reduce_pooling<TT, ROWWISE, UPDATE, false>(a, blocks, finish_blocks, prof, s);
 }
 
 }  // namespace
@@ -673,16 +673,22 @@ hipError_t launch_seg_reduce(const SegArgs& a, int64_t nnz_total, Profiler* prof
   int64_t nb = (nnz_total + groups_per_block - 1) / groups_per_block;
   if (nb > 256 * 32) nb = 256 * 32;
   const unsigned blocks = (unsigned)nb;
+  // one lane group per long run; there are at most nnz / threshold of them (blocks past the
+  // actual number leave at once)
+  int64_t fb = (nnz_total / (a.long_threshold > 0 ? a.long_threshold : 1) + groups_per_block) / groups_per_block;
+  if (fb < 64) fb = 64;
+  if (fb > 8192) fb = 8192;
+  const unsigned finish_blocks = (unsigned)fb;
   if (a.update) {
     if (a.table_bf16) {
-      if (a.rowwise) launch_reduce_variant<bf16_t, true, true>(a, blocks, prof, s);
-      else launch_reduce_variant<bf16_t, false, true>(a, blocks, prof, s);
+      if (a.rowwise) launch_reduce_variant<bf16_t, true, true>(a, blocks, finish_blocks, prof, s);
+      else launch_reduce_variant<bf16_t, false, true>(a, blocks, finish_blocks, prof, s);
     } else {
-      if (a.rowwise) launch_reduce_variant<float, true, true>(a, blocks, prof, s);
-      else launch_reduce_variant<float, false, true>(a, blocks, prof, s);
+      if (a.rowwise) launch_reduce_variant<float, true, true>(a, blocks, finish_blocks, prof, s);
+      else launch_reduce_variant<float, false, true>(a, blocks, finish_blocks, prof, s);
     }
   } else {
-    launch_reduce_variant<float, false, false>(a, blocks, prof, s);
+    launch_reduce_variant<float, false, false>(a, blocks, finish_blocks, prof, s);
   }
   return hipGetLastError();
 }
