@@ -1,6 +1,8 @@
 """HBM traffic per kernel class and training step from rocprofv3 counter runs.
 
     python paper_2404_09679_amd/pmc_summary.py <dir>
+    python paper_2404_09679_amd/pmc_summary.py --by-kernel <dir>     (any workload; no calibration runs needed:
+                                                                      FETCH_SIZE x 2, WRITE_SIZE x 1 as calibrated)
 
 <dir> holds four rocprofv3 --pmc outputs (csv), one counter each:
     bench_FETCH_SIZE/ bench_WRITE_SIZE/   python3 bench.py --steps 40 --warmup 10 --no-cpu-baseline
@@ -96,5 +98,23 @@ def mfma_summary(d, simds=1024, xcds=8):
         print(f"{c:18s} {busy[c]:17.0f} {active:14.0f} {100 * util:11.1f}% {mops.get(c, 0.0) * 512 / 1e9:14.2f}")
 
 
+def by_kernel(d, fscale=2.0, wscale=1.0):
+    """MB per launch of every kernel, from <d>/bench_FETCH_SIZE and <d>/bench_WRITE_SIZE."""
+    tot = collections.defaultdict(lambda: [0, 0.0, 0.0])
+    for sub, idx, scale in (("bench_FETCH_SIZE", 1, fscale), ("bench_WRITE_SIZE", 2, wscale)):
+        for r in _rows(f"{d}/{sub}"):
+            k = r["Kernel_Name"].replace("antdt::(anonymous namespace)::", "").replace("antdt::", "").replace("void ", "")
+            if idx == 1:
+                tot[k][0] += 1
+            tot[k][idx] += float(r["Counter_Value"]) * scale * 1024 / 1e6
+    print(f"{'kernel':72s} {'launches':>8s} {'fetched MB':>11s} {'written MB':>11s}   per launch")
+    for k, (n, f, w) in sorted(tot.items(), key=lambda kv: -(kv[1][1] + kv[1][2])):
+        if n and (f + w) / n >= 1.0 and "at::native" not in k and "fill_tables" not in k:
+            print(f"{k[:72]:72s} {n:8d} {f / n:11.1f} {w / n:11.1f}")
+
+
 if __name__ == "__main__":
-    main(sys.argv[1])
+    if sys.argv[1] == "--by-kernel":
+        by_kernel(sys.argv[2])
+    else:
+        main(sys.argv[1])
