@@ -31,12 +31,12 @@ MEASURED_TRAFFIC = {
     "cfg2": {
         "gemm_fwd": (73.7e6, "gemm.hip"), "gemm_bwd": (90.6e6, "gemm.hip"), "gemm_wgrad": (192.8e6, "gemm.hip"),
         "pool": (92.3e6, "embed.hip"),
-        "sparse_adagrad": (272.0e6, "coalesce.hip"), "seg_reduce_long": (1.5e6, "coalesce.hip"),
+        "sparse_adagrad": (272.1e6, "coalesce.hip"), "seg_reduce_long": (1.5e6, "coalesce.hip"),
         "dense_adagrad": (100.7e6, "optim.hip"),
     },
     "sha1": {"gemm.hip": "763734d5619304d69994a48d5d079a2878a9b88d",
              "embed.hip": "e8c218459c0d05e5dad1b82f3825f9b54cbda8df",
-             "coalesce.hip": "6cf580008c765311d078ac682a81ea9f007430e2",
+             "coalesce.hip": "7d88107b353aabbe3da1759050aee9258dae5900",
              "optim.hip": "398ec0d942ea14234c551490884f94a81795ca87"},
 }
 
