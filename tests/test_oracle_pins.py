@@ -534,6 +534,9 @@ def test_shard_queue_at_least_once_under_random_losses():
         t, d, dn = q.counts()
         assert t + d + dn == len(q.shards) and d == sum(len(h) for h in holding.values())
     assert np.all(seen == 1)                                   # every sample pushed exactly once here
+    # the data-integrity check of Section VII-D: whatever workers were lost on the way, the number
+    # of DONE shards at the end is ceil(N / (B M))
+    assert q.counts() == (0, 0, math.ceil(5003 / (7 * 13))) and len(q.shards) == 55
 
 
 def test_split_by_speed_rule_is_optimal_for_eq3():
