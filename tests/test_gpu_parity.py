@@ -37,6 +37,12 @@ WIDE = [wl.RankingConfig("rows-256B", 3, 3000, 64, "f32", "elementwise", 5, (197
 WIDE_HIDDEN = wl.RankingConfig("wide-hidden-bf16gemm", 4, 20_000, 32, "f32", "elementwise", 5, (133, 4096, 512, 1),
                                "bf16", 6, 1.1, (700, 37, 0, 863, 1000, 512, 640, 511, 513, 300, 1, 999, 256, 400, 500, 1000),
                                wl.SEED0 + 208)
+# the documented maxima at once: 128 fields, 8 weight layers, 64 shards (some empty), together with
+# the smallest row (4 columns: one lane per run)
+LIMITS = wl.RankingConfig("limits", 128, 300, 4, "f32", "elementwise", 3, (515, 32, 32, 24, 24, 16, 16, 8, 1), "f32",
+                          3, 1.1, tuple((k * 7) % 6 for k in range(64)), wl.SEED0 + 209, min_bag=0)
+LIMITS_BF = wl.scaled(LIMITS, name="limits-bf16", gemm_dtype="bf16", dim=8, table_dtype="bf16", adagrad_state="rowwise",
+                      layer_sizes=(1027, 32, 32, 24, 24, 16, 16, 8, 1))
 ONE_LAYER = wl.RankingConfig("single-layer", 3, 1000, 8, "f32", "elementwise", 2, (26, 1), "f32", 5, 1.05,
                              (40, 24), wl.SEED0 + 203, min_bag=0)
 
@@ -391,6 +397,15 @@ def test_ten_iterations_follow_the_oracle():
     for f in range(cfg.num_fields):
         assert rel_err(t[f * R:(f + 1) * R], tabs[f])[0] <= 1e-4, f"table {f} after ten iterations"
         assert rel_err(run.state.cpu().numpy()[f * R:(f + 1) * R], st[f])[0] <= 1e-4
+
+
+def test_documented_maxima():
+    # (accumulators start above zero: through eight narrow layers the gradients are of the order
+    # of eps, where the first step from a zero accumulator is lr*g/(|g|+eps) and amplifies the
+    # rounding of g; that regime has its own bound in the other tests)
+    check_iteration(LIMITS, LIMITS.shard_sizes, nonzero_state=True)
+    check_iteration(LIMITS, LIMITS.shard_sizes, batched=True, nonzero_state=True, batch_index=2)
+    check_iteration(LIMITS_BF, LIMITS_BF.shard_sizes, batched=True, nonzero_state=True, tol=TOLBF, bf16_gemm_oracle=True)
 
 
 def test_single_layer_model():
