@@ -408,6 +408,15 @@ def test_documented_maxima():
     check_iteration(LIMITS_BF, LIMITS_BF.shard_sizes, batched=True, nonzero_state=True, tol=TOLBF, bf16_gemm_oracle=True)
 
 
+def test_no_lookups_at_all():
+    """Every bag empty: the pooled part of the input is zero, no row is listed, the tables stay."""
+    cfg = wl.RankingConfig("no-lookups", 3, 100, 8, "f32", "elementwise", 4, (28, 8, 1), "f32", 0, 1.1, (5, 0, 7),
+                           wl.SEED0 + 210, min_bag=0)
+    run, agg = check_iteration(cfg, cfg.shard_sizes)
+    assert all(len(u) == 0 for u in agg.unique_ids) and all(len(c[0]) == 0 for c in run.coalesced)
+    check_iteration(cfg, cfg.shard_sizes, batched=True, mask=(0, 1, 1))
+
+
 def test_single_layer_model():
     check_iteration(ONE_LAYER, ONE_LAYER.shard_sizes)
 
