@@ -126,6 +126,8 @@ int antdt_bind(antdt_ctx* ctx, void* tables, float* table_state, float* mlp_para
  *                                          relative to field_ptr[f]; offsets[f][B] == nnz_f
  *   dense     DEVICE fp32  [B, num_dense]  (may be NULL when num_dense == 0)
  *   labels    DEVICE fp32  [B]             0 or 1
+ * Arrays without elements may be NULL (ids when there is no lookup; dense and labels when
+ * B == 0, which is legal: every following call then runs and changes nothing).
  * Only pointers and sizes are recorded; nothing is copied.  Resets the iteration state.
  * Requires antdt_bind.
  */

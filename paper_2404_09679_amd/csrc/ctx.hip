@@ -425,9 +425,9 @@ int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, 
                     const float* dense, const float* labels, int64_t B, void* stream) {
   if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_batch: null context");
   if (c->stage < ST_BOUND) return fail(c, ANTDT_BAD_STATE, "antdt_set_batch: call antdt_bind first");
-  if (!field_ptr || !offsets || !labels || (c->m.num_dense > 0 && !dense))
-    return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: null buffer");
   if (B < 0 || B > c->m.max_batch) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: B out of range");
+  if (!field_ptr || !offsets || (B > 0 && (!labels || (c->m.num_dense > 0 && !dense))))
+    return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: null buffer");
   const int F = c->m.num_fields;
   if (field_ptr[0] != 0) return fail(c, ANTDT_INVALID_ARG, "antdt_set_batch: field_ptr[0] != 0");
   for (int f = 0; f < F; ++f)

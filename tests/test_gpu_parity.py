@@ -417,6 +417,23 @@ def test_no_lookups_at_all():
     check_iteration(cfg, cfg.shard_sizes, batched=True, mask=(0, 1, 1))
 
 
+def test_empty_batch():
+    """B = 0: every call is legal, nothing is listed and nothing changes."""
+    import dataclasses
+    from gpu_helpers import GpuRun
+    cfg = dataclasses.replace(SMALL, name="empty-batch", shard_sizes=(0, 0))
+    tables, state, flat, fstate, batch = make_inputs(cfg)
+    assert batch.batch == 0
+    for batched in (False, True):
+        run = GpuRun(cfg, tables, flat, state, fstate, max_batch=4, max_shards=2)
+        run.set_batch(batch)
+        run.iteration(cfg.shard_sizes, batched=batched)
+        assert all(len(c[0]) == 0 and list(c[1]) == [0] for c in run.coalesced)
+        assert np.all(run.g_dense == 0) and np.all(run.loss.cpu().numpy() == 0)
+        assert np.array_equal(run.tables.cpu().numpy(), tables) and np.array_equal(run.params.cpu().numpy(), flat)
+        assert np.all(run.state.cpu().numpy() == 0) and np.all(run.pstate.cpu().numpy() == 0)
+
+
 def test_single_layer_model():
     check_iteration(ONE_LAYER, ONE_LAYER.shard_sizes)
 
