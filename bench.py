@@ -36,7 +36,7 @@ MEASURED_TRAFFIC = {
     },
     "sha1": {"gemm.hip": "763734d5619304d69994a48d5d079a2878a9b88d",
              "embed.hip": "e8c218459c0d05e5dad1b82f3825f9b54cbda8df",
-             "coalesce.hip": "7d88107b353aabbe3da1759050aee9258dae5900",
+             "coalesce.hip": "6bf54643af44bb7717d746ea9702d1d219c704a5",
              "optim.hip": "398ec0d942ea14234c551490884f94a81795ca87"},
 }
 

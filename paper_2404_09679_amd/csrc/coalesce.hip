@@ -246,7 +246,7 @@ __global__ __launch_bounds__(SORT_THREADS) void seg_heads_kernel(SegArgs a, Fiel
 
 // One block: exclusive prefix over all tiles (-> first unique of every tile and field),
 // the terminal segment offset of every field, the per-sample aggregation weight, and the
-// reset of the long-segment queue.
+// reset of the two list lengths (long runs, chunks) that seg_queue_kernel counts up.
 __global__ __launch_bounds__(1024) void seg_scan_kernel(SegArgs a, FieldPtr fp, TileBase tb, ShardTab tab) {
   __shared__ int wsum[16];
   const int n = a.total_tiles;
