@@ -25,8 +25,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per step and kernel class of the config-2 workload, from rocprofv3 counter runs
 # (FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy kernel's reading).  A class's entry
-# is only reported while the source file of its kernels still has the fingerprint it had
-# when the counters were taken.
+# is only reported while the code of the source file of its kernels (comments and white space
+# aside) still has the fingerprint it had when the counters were taken.
 MEASURED_TRAFFIC = {
     "cfg2": {
         "gemm_fwd": (73.7e6, "gemm.hip"), "gemm_bwd": (90.6e6, "gemm.hip"), "gemm_wgrad": (192.8e6, "gemm.hip"),
@@ -34,25 +34,33 @@ MEASURED_TRAFFIC = {
         "sparse_adagrad": (272.1e6, "coalesce.hip"), "seg_reduce_long": (1.5e6, "coalesce.hip"),
         "dense_adagrad": (100.7e6, "optim.hip"),
     },
-    "sha1": {"gemm.hip": "763734d5619304d69994a48d5d079a2878a9b88d",
-             "embed.hip": "e8c218459c0d05e5dad1b82f3825f9b54cbda8df",
-             "coalesce.hip": "6bf54643af44bb7717d746ea9702d1d219c704a5",
-             "optim.hip": "398ec0d942ea14234c551490884f94a81795ca87"},
+    "sha1": {"gemm.hip": "5de0dd76a699c9826bd9f2a88656383688aeca47",
+             "embed.hip": "2ab400f86171f3c0a2539f685328e0b9611bdaef",
+             "coalesce.hip": "36661ca5f13ea0175ab0003d4c43bfd419091a96",
+             "optim.hip": "79090e5f4d378e258fa3538b8574f6e9a57c6998"},
 }
 
 
+def _code_fingerprint(path):
+    """sha1 of a source file's code: comments removed, white space collapsed."""
+    import re
+    try:
+        text = open(path, encoding="utf-8").read()
+    except OSError:
+        return None
+    text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+    text = re.sub(r"//[^\n]*", " ", text)
+    return hashlib.sha1(" ".join(text.split()).encode()).hexdigest()
+
+
 def _measured_traffic(workload, kernel_class, launches_per_step):
-    import hashlib
     entry = MEASURED_TRAFFIC.get(workload, {}).get(kernel_class)
     if entry is None:
         return None
     nbytes, src = entry
     path = os.path.join(ROOT, "paper_2404_09679_amd", "csrc", src)
-    try:
-        sha = hashlib.sha1(open(path, "rb").read()).hexdigest()
-    except OSError:
-        return None
-    if sha != MEASURED_TRAFFIC["sha1"].get(src):
+    sha = _code_fingerprint(path)
+    if sha is None or sha != MEASURED_TRAFFIC["sha1"].get(src):
         return None
     return nbytes / max(launches_per_step, 1e-9)
 
