@@ -196,6 +196,7 @@ struct HeadReduceArgs {
   const bf16_t* ht;     // optional transposed activation [width, ldt]: selects the coalesced kernel
   int64_t ldh, ldt, P, w_off, b_off;
   int32_t width, bf16_h, k_begin, k_end;
+  int32_t part;         // transposed-activation kernel only: 0 everything, 1 the weight sums, 2 bias sum and loss
 };
 hipError_t launch_head_reduce(const HeadReduceArgs& a, const ShardTab& tab, hipStream_t s);
 

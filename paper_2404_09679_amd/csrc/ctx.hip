@@ -144,6 +144,8 @@ struct antdt_ctx {
   bool included[ANTDT_MAX_SHARDS] = {};
   double shard_scale[ANTDT_MAX_SHARDS];  // per-worker factor on the aggregation weight (1 unless set)
   bool weights_dirty = false;            // the factors changed after the weights were last formed
+  bool head_weights_deferred = false;    // the last layer's weight sums of this worker step are still to be launched
+  HeadReduceArgs head_reduce_args;
   int sorted_buf = 0;
   // side stream on which the coalescing structure of a batch is built while the MLP runs
   hipStream_t side = nullptr;
@@ -692,10 +694,16 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       r.ht = c->act_t[L - 1];
       r.ldt = c->ldt;
     }
+    // With a weight-gradient stream, only the bias sum and the shard losses stay on the launch
+    // stream (one wavefront per shard); the weight sums of the last layer, which nothing needs
+    // before the dense update, are computed on that stream ahead of the other weight gradients.
+    c->head_weights_deferred = r.ht != nullptr && L > 1 && c->wside != nullptr;
+    r.part = c->head_weights_deferred ? 2 : 0;
     {
       ProfScope ps(pr, KID_HEAD_REDUCE, s);
       HIP_TRY(c, launch_head_reduce(r, tab, s));
     }
+    c->head_reduce_args = r;
     if (c->act_bf16 && L > 1 && !head_writes_dht) {  // the weight-gradient product wants dh^T
       TransposeArgs t;
       memset(&t, 0, sizeof(t));
@@ -785,6 +793,13 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
         if (l == 0) bwd_scope.close();
         HIP_TRY(c, hipEventRecord(c->ev_dh[l], s));
         HIP_TRY(c, hipStreamWaitEvent(ws, c->ev_dh[l], 0));
+        if (c->head_weights_deferred) {  // (first release: everything the loss kernel wrote is behind this event)
+          HeadReduceArgs r = c->head_reduce_args;
+          r.part = 1;
+          ProfScope ps(pr, KID_HEAD_REDUCE, ws);
+          HIP_TRY(c, launch_head_reduce(r, tab, ws));
+          c->head_weights_deferred = false;
+        }
       }
       for (const int last = l > 0 ? l - 1 : 0; next_w >= last; --next_w) {
         const int rc = weight_gradient(next_w);

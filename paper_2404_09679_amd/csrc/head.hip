@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void head_reduce_t_kernel(HeadReduceArgs a, Sh
   const int64_t s0 = tab.start[k];
   const int n = tab.len[k];
   const int lane = threadIdx.x & 63;
-  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int j = a.part == 2 ? a.width + (int)(threadIdx.x >> 6) : blockIdx.x * 4 + (int)(threadIdx.x >> 6);
   float* g = a.grads + (int64_t)k * a.P;
   if (j < a.width) {
     const bf16_t* h = a.ht + (int64_t)j * a.ldt + s0;
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void head_reduce_t_kernel(HeadReduceArgs a, Sh
     for (int s = lane; s < n; s += 64) acc = fmaf(bf2f(h[s]), a.dz[s0 + s], acc);
     acc = wave_sum(acc);
     if (lane == 0) g[a.w_off + j] = acc;
-  } else if (j == a.width) {
+  } else if (j == a.width && a.part != 1) {
     float sdz = 0.0f, sl = 0.0f;
 #pragma unroll 4
     for (int s = lane; s < n; s += 64) {
@@ -243,7 +243,8 @@ hipError_t launch_head(const HeadArgs& a, const ShardTab& tab, hipStream_t s) {
 
 hipError_t launch_head_reduce(const HeadReduceArgs& a, const ShardTab& tab, hipStream_t s) {
   if (a.ht) {
-    hipLaunchKernelGGL(head_reduce_t_kernel, dim3((a.width + 1 + 3) / 4, a.k_end - a.k_begin), dim3(256), 0, s, a, tab);
+    const unsigned bx = a.part == 2 ? 1u : (unsigned)((a.width + (a.part == 1 ? 0 : 1) + 3) / 4);
+    hipLaunchKernelGGL(head_reduce_t_kernel, dim3(bx, a.k_end - a.k_begin), dim3(256), 0, s, a, tab);
     return hipGetLastError();
   }
   dim3 grid((a.width + 63) / 64, a.k_end - a.k_begin), block(256);
