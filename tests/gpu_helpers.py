@@ -6,7 +6,6 @@ import numpy as np
 import torch
 
 import paper_2404_09679_amd as A
-import workload as wl
 
 DEV = "cuda:0"
 

@@ -9,7 +9,7 @@ import torch
 
 import oracle
 import workload as wl
-from helpers import BF16_MAX_TOL, assert_close, flat_dense_grad, flat_layers, rel_err
+from helpers import BF16_MAX_TOL, assert_close, flat_dense_grad, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL32, TOLBF = 1e-5, 2e-2
