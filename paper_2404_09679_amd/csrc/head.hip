@@ -50,12 +50,19 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a, ShardTab tab) {
 // bf16 variant working on a tile of `spb` samples staged in LDS, so that the gradient can be
 // written both row-major (dh) and transposed (dht, sample index contiguous) with coalesced
 // stores; same arithmetic as head_kernel.
-constexpr int HEAD_LDS_ELEMS = 16448;  // 32 x (512 + 2) bf16
+constexpr int HEAD_LDS_ELEMS = 16448;  // largest tile: 32 x (512 + 2) bf16
+// Shared memory is sized at the launch to the tile actually used (spb x (width + 2) bf16, the
+// last-layer weights, spb floats), so that small widths leave room for many blocks per
+// compute unit: the kernel is a chain of dependent global round trips and needs them in flight.
+__host__ __device__ inline size_t head_tile_lds_bytes(int spb, int width) {
+  return (((size_t)spb * (width + 2) * 2 + 15) & ~(size_t)15) + (size_t)width * 4 + 32 * 4;
+}
 __global__ __launch_bounds__(256) void head_tile_kernel(HeadArgs a, ShardTab tab, int spb) {
-  __shared__ __attribute__((aligned(16))) bf16_t tile[HEAD_LDS_ELEMS];
-  __shared__ float dzs[32];
-  __shared__ float wl[4096];  // last-layer weights (global loads inside the store loops would serialise)
+  extern __shared__ __attribute__((aligned(16))) char head_lds[];
   const int width = a.width, pitch = width + 2, vpr = width >> 3;
+  bf16_t* tile = reinterpret_cast<bf16_t*>(head_lds);
+  float* wl = reinterpret_cast<float*>(head_lds + (((size_t)spb * pitch * 2 + 15) & ~(size_t)15));  // last-layer weights
+  float* dzs = wl + width;
   for (int j = threadIdx.x; j < width; j += 256) wl[j] = a.w[j];
   const int64_t first = tab.start[a.k_begin];
   const int64_t last = (int64_t)tab.start[a.k_end - 1] + tab.len[a.k_end - 1];
@@ -229,7 +236,8 @@ hipError_t launch_head(const HeadArgs& a, const ShardTab& tab, hipStream_t s) {
   if (a.dht) {  // bf16 hidden activation with a transposed gradient copy: tile kernel
     int spb = 16;
     while (spb > 4 && spb * (a.width + 2) > HEAD_LDS_ELEMS) spb >>= 1;
-    hipLaunchKernelGGL(head_tile_kernel, dim3((unsigned)((last - first + spb - 1) / spb)), block, 0, s, a, tab, spb);
+    hipLaunchKernelGGL(head_tile_kernel, dim3((unsigned)((last - first + spb - 1) / spb)), block,
+                       head_tile_lds_bytes(spb, a.width), s, a, tab, spb);
     return hipGetLastError();
   }
   if (a.bf16_h) {
