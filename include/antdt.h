@@ -251,7 +251,8 @@ int antdt_expand_accumulation(int32_t k, const int32_t* n, const int64_t* B_i, c
                               int32_t* count_out);
 
 /*
- * Shard queue with states (Section V-B, the stateful dynamic data sharding service).  The N
+ * Shard queue with states (Section V-C, the stateful dynamic data sharding service: the shard
+ * arithmetic of Section V-C.1, the states and the re-queue of Section V-C.3).  The N
  * samples of a data set are cut into K = ceil(N / (B*M)) shards of M batches, each a pair
  * (start offset, length); only the last may be short.  All shards start as TODO, in a queue in
  * index order.  antdt_dds_fetch hands the head of the queue to a worker (TODO -> DOING; EMPTY when

@@ -1,5 +1,5 @@
 """Host-side parts of the framework around the iteration: the shard queue with states
-(Section V-B) and an iteration-level model of bulk-synchronous training under injected
+(Section V-C: shard arithmetic V-C.1, states and re-queue V-C.3) and an iteration-level model of bulk-synchronous training under injected
 stragglers (Section II, Eq. 1; Section VI-A; Section VII-A.2).
 
 Test infrastructure: see the package docstring.
@@ -48,7 +48,7 @@ BSP, ADJUST_BS, BACKUP_WORKERS, ANTDT_ND = 0, 1, 2, 3
 
 
 class ShardQueue:
-    """Stateful dynamic data sharding (Section V-B)."""
+    """Stateful dynamic data sharding (Section V-C.1 shards, Section V-C.3 states)."""
 
     def __init__(self, N: int, B: int, M: int):
         self.shards = data_shards(N, B, M)

@@ -202,6 +202,7 @@ class Context:
             pad = (-workspace.data_ptr()) % 256
             workspace = workspace[pad:pad + self.workspace_bytes()]
         self.workspace = workspace
+        self._device = tables.device
         self._keep.update(tables=tables, table_state=table_state, mlp_params=mlp_params,
                           mlp_state=mlp_state, workspace=workspace)
         self._check(lib.antdt_bind(self._h, _ptr(tables), _ptr(table_state), _ptr(mlp_params),
@@ -264,7 +265,7 @@ class Context:
         x, rows, ld, dt = C.c_void_p(), C.c_int64(), C.c_int64(), C.c_int32()
         self._check(lib.antdt_view_pooled(self._h, k, C.byref(x), C.byref(rows), C.byref(ld), C.byref(dt)))
         if rows.value == 0:
-            return torch.empty((0, ld.value), device=self.workspace.device)
+            return torch.empty((0, ld.value), device=self._device)
         dtype, es = (torch.bfloat16, 2) if dt.value == BF16 else (torch.float32, 4)
         return self._ws_view(x.value, rows.value * ld.value * es, dtype).reshape(rows.value, ld.value)
 
@@ -276,7 +277,7 @@ class Context:
         dense = self._ws_view(d.value, P * 4, torch.float32)
         n = self.shards[k][1]
         gx = (self._ws_view(dx.value, n * ld.value * 4, torch.float32).reshape(n, ld.value) if n
-              else torch.empty((0, ld.value), device=self.workspace.device))
+              else torch.empty((0, ld.value), device=self._device))
         return dense, gx
 
     def view_dense_grad(self) -> torch.Tensor:
@@ -292,7 +293,7 @@ class Context:
         self._check(lib.antdt_view_coalesced(self._h, f, C.byref(u), C.byref(so), C.byref(ss), C.byref(nu),
                                              C.byref(nnz), C.byref(G), _stream()))
         U, n, D = nu.value, nnz.value, self.model.dim
-        dev = self.workspace.device
+        dev = self._device
         uniq = self._ws_view(u.value, U * 4, torch.int32) if U else torch.empty(0, dtype=torch.int32, device=dev)
         segoff = self._ws_view(so.value, (U + 1) * 4, torch.int32)
         samples = self._ws_view(ss.value, n * 4, torch.int32) if n else torch.empty(0, dtype=torch.int32, device=dev)
@@ -382,7 +383,7 @@ def _raise(rc: int):
 
 
 class ShardQueue:
-    """The shard queue with states of Section V-B (see antdt_dds_* in antdt.h)."""
+    """The shard queue with states of Section V-C (see antdt_dds_* in antdt.h)."""
 
     def __init__(self, N: int, B: int, M: int):
         h = C.c_void_p()

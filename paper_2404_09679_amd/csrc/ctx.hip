@@ -156,7 +156,8 @@ struct antdt_ctx {
   hipEvent_t ev_dh[ANTDT_MAX_LAYERS + 1] = {};  // ev_dh[l]: dH_l (and its transposed copy) is ready
   hipEvent_t ev_wgrad = nullptr;                // all weight gradients of the last worker step are written
   bool wgrad_pending = false;
-  bool presorted = false;
+  bool presorted = false;     // the coalescing structure of the current batch and split is built (or being built)
+  bool side_pending = false;  // work is in flight on the side stream that no other stream has waited for yet
 };
 
 static int fail(antdt_ctx* c, int code, const std::string& msg) {
@@ -238,6 +239,27 @@ static size_t carve(antdt_ctx* c, char* base) {
   c->partial = (float*)take((size_t)c->item_cap * m.dim * 4);
   c->G = (float*)take((size_t)N * m.dim * 4);
   return off;
+}
+
+// Makes `s` wait for whatever the side stream is still doing (it writes the sort buffers, the run
+// tables and the per-sample weights, and reads the sample index of every lookup): before anything
+// rebuilds or overwrites those.  Whether that structure is still valid is a separate question.
+static int join_side(antdt_ctx* c, hipStream_t s) {
+  if (c->side_pending) {
+    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
+    c->side_pending = false;
+  }
+  return ANTDT_OK;
+}
+
+// Makes `s` wait for the weight-gradient products of the last worker step (they run on their
+// own stream): before anything reads the per-shard dense gradients or overwrites their operands.
+static int join_wgrad(antdt_ctx* c, hipStream_t s) {
+  if (c->wgrad_pending) {
+    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_wgrad, 0));
+    c->wgrad_pending = false;
+  }
+  return ANTDT_OK;
 }
 
 extern "C" {
@@ -447,7 +469,10 @@ int antdt_set_batch(antdt_ctx* c, const int32_t* ids, const int64_t* field_ptr, 
   c->labels = labels;
   c->B = B;
   c->stage = ST_BATCH;
-  if (c->presorted) HIP_TRY(c, hipStreamWaitEvent((hipStream_t)stream, c->ev_join, 0));
+  {
+    const int rc = join_side(c, (hipStream_t)stream);
+    if (rc) return rc;
+  }
   c->presorted = false;
   memset(c->stepped, 0, sizeof(c->stepped));
   return ANTDT_OK;
@@ -581,23 +606,14 @@ static int build_coalescing(antdt_ctx* c, const int32_t* ids, const int32_t* pay
   return ANTDT_OK;
 }
 
-// Makes `s` wait for the weight-gradient products of the last worker step (they run on their
-// own stream): before anything reads the per-shard dense gradients or overwrites their operands.
-static int join_wgrad(antdt_ctx* c, hipStream_t s) {
-  if (c->wgrad_pending) {
-    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_wgrad, 0));
-    c->wgrad_pending = false;
-  }
-  return ANTDT_OK;
-}
-
 // Forward and backward of shards [k0, k1) as one batched sequence of launches.
 static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream_t s) {
   if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_worker_step: call antdt_set_batch first");
   if (!c->have_shards || c->shard_B != c->B)
     return fail(c, ANTDT_BAD_STATE, "antdt_worker_step: antdt_assign_shard with the batch's B is required");
-  if (c->presorted) {  // an earlier batched step whose aggregate never came: let its side work finish
-    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  {  // an earlier batched step whose aggregate never came (or whose split was replaced): let its side work finish
+    const int rc = join_side(c, s);
+    if (rc) return rc;
     c->presorted = false;
   }
   {  // this step overwrites the operands of the previous step's weight-gradient products
@@ -635,6 +651,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     if (rc) return rc;
     HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
     c->presorted = true;
+    c->side_pending = true;
   }
   auto act = [&](int l) -> char* { return l == 0 ? c->x : c->h[l]; };
   auto ld = [&](int l) -> int64_t { return l == 0 ? c->ldx : c->width[l]; };
@@ -844,7 +861,10 @@ int antdt_aggregate(antdt_ctx* c, const uint8_t* shard_mask, void* stream) {
   }
   bool all = true;  // leaving out an empty shard changes nothing
   for (int k = 0; k < K; ++k) all = all && (c->included[k] || c->tab.len[k] == 0);
-  if (c->presorted) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  {  // also when the structure built there is stale (a new split): its buffers are rebuilt below
+    const int rc = join_side(c, s);
+    if (rc) return rc;
+  }
   if (c->presorted && all && !c->weights_dirty) {
     // the batched worker step already built the structure on the side stream
   } else if (all) {

@@ -1,5 +1,5 @@
 // Host-side parts of the framework around the iteration (no GPU work):
-//  * the shard queue with states of Section V-B: N samples cut into K = ceil(N / (B*M)) shards
+//  * the shard queue with states of Section V-C (V-C.1 shards, V-C.3 states and re-queue): N samples cut into K = ceil(N / (B*M)) shards
 //    (start, length), TODO -> DOING (fetched by a worker) -> DONE (its gradients were pushed);
 //    the DOING shards of a lost worker go back to TODO at the END of the queue;
 //  * an iteration-level model of bulk-synchronous training under injected stragglers: one

@@ -1,7 +1,7 @@
 """HBM traffic per kernel class and training step from rocprofv3 counter runs.
 
-    python paper_2404_09679_amd/pmc_summary.py <dir>
-    python paper_2404_09679_amd/pmc_summary.py --by-kernel <dir>     (any workload; no calibration runs needed:
+    python pmc_summary.py <dir>
+    python pmc_summary.py --by-kernel <dir>     (any workload; no calibration runs needed:
                                                                       FETCH_SIZE x 2, WRITE_SIZE x 1 as calibrated)
 
 <dir> holds four rocprofv3 --pmc outputs (csv), one counter each:

@@ -165,9 +165,8 @@ def test_config3_heterogeneous_shards_full_size():
 
 def test_config4_bf16_tables_rowwise_state_full_size():
     """128 GB of bf16 tables, one Adagrad accumulator per row, 41.8 M lookups per iteration.
-    The oracle runs four of the sixteen shards (per-shard gradients, and the coalesced
-    gradient of every row that only those shards touch); structure and update are checked
-    on all rows."""
+    The oracle runs all sixteen shards on the touched rows; rows the batch does not touch are
+    checked on a sample of `check_rows` rows and on the neighbours of every touched row."""
     run_fullsize(wl.CONFIGS[4], check_rows=100_000)
 
 

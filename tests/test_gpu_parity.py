@@ -64,7 +64,7 @@ def make_inputs(cfg, nonzero_state=False, batch_index=0):
 
 
 def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, fwd_tol=None,
-                    bf16_gemm_oracle=None, batch_index=0, mask=None, scale=None, scale_late=False):
+                    bf16_gemm_oracle=None, batch_index=0, mask=None, scale=None, scale_late=False, prelude=None):
     """Run one full iteration on the GPU and with the oracle; compare every result.
     `tol` bounds gradients and updates, `fwd_tol` (default: tol) the forward results."""
     from gpu_helpers import GpuRun
@@ -75,6 +75,8 @@ def check_iteration(cfg, sizes, nonzero_state=False, batched=False, tol=TOL32, f
                                             mask=mask, bf16_gemm=bf16_gemm_oracle, want_samples=True, scale=scale)
     run = GpuRun(cfg, tables, flat, state, fstate, max_batch=batch.batch, max_shards=len(sizes))
     run.set_batch(batch)
+    if prelude is not None:
+        prelude(run)
     run.iteration(sizes, batched=batched, mask=mask, scale=scale, scale_late=scale_late)
     F, D, R = cfg.num_fields, cfg.dim, cfg.rows_per_field
     W = cfg.input_width
@@ -256,6 +258,20 @@ def test_masked_then_full_aggregation_of_the_same_batch():
         assert np.array_equal(so.astype(np.int64), agg.seg_offsets[f])
         assert_close(G, agg.G[f], TOL32, f"coalesced gradient, field {f}")
         assert len(masked[f]) <= len(u)
+
+
+def test_new_split_after_a_batched_step():
+    """A batched worker step starts building the coalescing structure of its split on the
+    library's side stream; a new split of the same batch (ADJUST_BS between the step and the
+    aggregation) followed by per-shard steps must wait for that work before the structure is
+    built again in the same buffers, and must not use the old one."""
+    def batched_step_with_another_split(run):
+        K = run.model.max_shards
+        run.ctx.assign_shard(run.batch.batch, K)     # equal split
+        run.ctx.worker_step_all(torch.zeros(K, device="cuda:0"))
+    check_iteration(MID, (500, 0, 250, 250), prelude=batched_step_with_another_split)
+    check_iteration(MID, (100, 900), batched=True, mask=(0, 1), prelude=batched_step_with_another_split)
+    check_iteration(MID_BF, (640, 360), tol=TOLBF, bf16_gemm_oracle=True, prelude=batched_step_with_another_split)
 
 
 def test_gradient_accumulation_plan_as_micro_batch_shards():

@@ -200,7 +200,7 @@ def test_expand_accumulation_lists_micro_batches_device_by_device():
     assert A.expand_accumulation((1,), (5,), (0,)) == ([], [])
 
 
-# ------------------------------------------------------------------ shard queue (Section V-B)
+# ------------------------------------------------------------------ shard queue (Section V-C)
 def test_shard_queue_matches_the_oracle_step_by_step():
     rng = np.random.default_rng(17)
     for N, B, M in [(5003, 7, 13), (100, 10, 10), (1, 4, 100), (0, 3, 2), (999, 1, 1)]:

@@ -486,7 +486,7 @@ def test_eq4_bruteforce():
 
 # ------------------------------------------------------------------ shard queue and training model
 def test_shard_queue_states_and_requeue_at_the_tail():
-    """Section V-B: shards (start, length) in index order; fetch TODO -> DOING, report -> DONE,
+    """Section V-C.1 and V-C.3: shards (start, length) in index order; fetch TODO -> DOING, report -> DONE,
     a lost worker's DOING shards go back to TODO at the END of the queue."""
     q = oracle.ShardQueue(N=1050, B=10, M=10)                 # K = ceil(1050 / 100) = 11, last one short
     assert q.shards == oracle.data_shards(1050, 10, 10) and len(q.shards) == 11 and q.shards[-1] == (1000, 50)
