@@ -40,6 +40,7 @@ extern "C" {
 #define ANTDT_MAX_LAYERS 8
 #define ANTDT_MAX_FIELDS 128
 #define ANTDT_MAX_SHARDS 64
+#define ANTDT_STATIC_SCRATCH_BYTES (32u << 20) /* scratch of antdt_bind_static, per device */
 
 enum {
   ANTDT_OK = 0,
@@ -116,6 +117,32 @@ int antdt_workspace_bytes(const antdt_ctx* ctx, size_t* bytes);
  */
 int antdt_bind(antdt_ctx* ctx, void* tables, float* table_state, float* mlp_params,
                float* mlp_state, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * antdt_bind for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same attachment of the caller's tables,
+ * table_state, mlp_params and mlp_state (DEVICE, 16-byte aligned, as for antdt_bind), but the
+ * workspace is a static device buffer inside the library, ANTDT_STATIC_SCRATCH_BYTES (32 MiB)
+ * on every device the library is used on, held until the process ends.  The call and every later
+ * call on the context allocate nothing: no hipMalloc / hipFree, no stream, no event.  All
+ * kernels of the iteration are therefore enqueued on the caller's stream, one after the other
+ * (antdt_bind's contexts run the sort and the weight gradients on streams of the library); the
+ * results are the same.
+ *   - ANTDT_WORKSPACE_TOO_SMALL when antdt_workspace_bytes(ctx) exceeds the buffer; the message
+ *     names both sizes.  Nothing is touched in that case.
+ *   - The buffer belongs to the device that is current at the call; the context must be used
+ *     with that device current.
+ *   - One buffer per device serves every context bound this way.  It keeps whatever the last
+ *     user left in it; the library initialises every part before reading it, so nothing needs
+ *     clearing.  Binding a second context takes the buffer away from the first: the first
+ *     context's calls return ANTDT_BAD_STATE until it is bound again.  Two such contexts must
+ *     not be used in overlapping calls or on streams that run concurrently: they would race
+ *     on the buffer.
+ *   - antdt_aggregate with a mask still waits for the stream once, antdt_validate_batch and the
+ *     views still synchronise as documented; none of them allocates.
+ */
+int antdt_bind_static(antdt_ctx* ctx, void* tables, float* table_state, float* mlp_params,
+                      float* mlp_state, void* stream);
 
 /*
  * Present one global batch of B samples (B <= max_batch) in CSR form per field:

@@ -23,7 +23,7 @@ EXPORTS = [
     "antdt_view_pooled", "antdt_view_shard_grads", "antdt_view_dense_grad", "antdt_view_coalesced",
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
     "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr", "antdt_validate_batch",
-    "antdt_set_shard_scale", "antdt_stream_copy", "antdt_profile_overhead",
+    "antdt_set_shard_scale", "antdt_stream_copy", "antdt_profile_overhead", "antdt_bind_static",
     "antdt_dds_create", "antdt_dds_destroy", "antdt_dds_num_shards", "antdt_dds_fetch", "antdt_dds_report_done",
     "antdt_dds_release_worker", "antdt_dds_shard", "antdt_dds_counts", "antdt_simulate_bsp",
 ]
@@ -73,6 +73,7 @@ def _load():
     lib.antdt_last_error.restype = C.c_char_p
     lib.antdt_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
     lib.antdt_bind.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.antdt_bind_static.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.antdt_set_batch.argtypes = [vp, vp, C.POINTER(i64), vp, vp, vp, i64, vp]
     lib.antdt_assign_shard.argtypes = [vp, i64, i32, C.POINTER(i64), C.POINTER(C.c_double),
                                        C.POINTER(i64), C.POINTER(i64)]
@@ -163,6 +164,13 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
+class _RawDeviceBytes:
+    """nbytes of device memory at ptr, for torch.as_tensor (no copy, no ownership)."""
+
+    def __init__(self, ptr: int, nbytes: int):
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False), "version": 2}
+
+
 class Context:
     """One model bound to caller-owned device tensors.  Methods mirror the C calls."""
 
@@ -207,6 +215,15 @@ class Context:
                           mlp_state=mlp_state, workspace=workspace)
         self._check(lib.antdt_bind(self._h, _ptr(tables), _ptr(table_state), _ptr(mlp_params),
                                    _ptr(mlp_state), _ptr(workspace), workspace.numel(), _stream()))
+
+    def bind_static(self, tables, table_state, mlp_params, mlp_state):
+        """antdt_bind_static: the library's static device buffer is the workspace (no allocation)."""
+        self.workspace = None
+        self._device = tables.device
+        self._keep.update(tables=tables, table_state=table_state, mlp_params=mlp_params, mlp_state=mlp_state,
+                          workspace=None)
+        self._check(lib.antdt_bind_static(self._h, _ptr(tables), _ptr(table_state), _ptr(mlp_params),
+                                          _ptr(mlp_state), _stream()))
 
     def set_batch(self, ids, field_ptr: Sequence[int], offsets, dense, labels):
         F = self.model.num_fields
@@ -257,6 +274,8 @@ class Context:
 
     # ------------------------------------------------------------- views
     def _ws_view(self, ptr: int, nbytes: int, dtype) -> torch.Tensor:
+        if self.workspace is None:   # bound to the library's static buffer: wrap the raw device memory
+            return torch.as_tensor(_RawDeviceBytes(ptr, nbytes), device=self._device).view(dtype)
         off = ptr - self.workspace.data_ptr()
         assert 0 <= off and off + nbytes <= self.workspace.numel(), "view outside the workspace"
         return self.workspace[off:off + nbytes].view(dtype)

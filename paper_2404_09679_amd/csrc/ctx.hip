@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -158,7 +159,15 @@ struct antdt_ctx {
   bool wgrad_pending = false;
   bool presorted = false;     // the coalescing structure of the current batch and split is built (or being built)
   bool side_pending = false;  // work is in flight on the side stream that no other stream has waited for yet
+  // bound by antdt_bind_static: the workspace is the library's static device buffer and every
+  // kernel goes to the caller's stream (no library-owned stream or event exists or is created)
+  bool static_bound = false;
+  int static_device = -1;
 };
+
+// The library's own streams, or none when the context works on the caller's stream only.
+static inline hipStream_t side_stream(const antdt_ctx* c) { return c->static_bound ? nullptr : c->side; }
+static inline hipStream_t wgrad_stream(const antdt_ctx* c) { return c->static_bound ? nullptr : c->wside; }
 
 static int fail(antdt_ctx* c, int code, const std::string& msg) {
   if (c) c->err = msg;
@@ -239,6 +248,28 @@ static size_t carve(antdt_ctx* c, char* base) {
   c->partial = (float*)take((size_t)c->item_cap * m.dim * 4);
   c->G = (float*)take((size_t)N * m.dim * 4);
   return off;
+}
+
+// ----------------------------------------------------------------------------------------
+// Scratch of antdt_bind_static, the entry point for callers that cannot allocate.  The array's
+// name is only a host-side handle; kernels and copies get the address that
+// hipGetSymbolAddress reports for the device that is current, looked up once per device (each
+// device holds its own copy of the array at its own address).
+static __device__ __align__(256) unsigned char scratch[ANTDT_STATIC_SCRATCH_BYTES];
+
+static constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[MAX_DEVICES] = {};
+static antdt_ctx* g_scratch_owner[MAX_DEVICES] = {};  // context whose workspace the buffer currently is
+
+// A context that gives the static buffer up (rebound to a caller's workspace, or destroyed).
+static void release_static(antdt_ctx* c) {
+  if (!c->static_bound) return;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (c->static_device >= 0 && c->static_device < MAX_DEVICES && g_scratch_owner[c->static_device] == c)
+    g_scratch_owner[c->static_device] = nullptr;
+  c->static_bound = false;
+  c->static_device = -1;
 }
 
 // Makes `s` wait for whatever the side stream is still doing (it writes the sort buffers, the run
@@ -329,6 +360,7 @@ int antdt_create(const antdt_model* model, antdt_ctx** out) {
 
 int antdt_destroy(antdt_ctx* ctx) {
   if (!ctx) return ANTDT_OK;
+  release_static(ctx);
   prof_drain(&ctx->prof);
   if (ctx->side) {
     (void)hipStreamSynchronize(ctx->side);
@@ -406,6 +438,7 @@ int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params
   if (((uintptr_t)workspace & 255) || ((uintptr_t)tables & 15) || ((uintptr_t)table_state & 15) ||
       ((uintptr_t)mlp_params & 15) || ((uintptr_t)mlp_state & 15))
     return fail(c, ANTDT_INVALID_ARG, "antdt_bind: misaligned buffer (workspace 256 B, others 16 B)");
+  release_static(c);
   c->tables = tables;
   c->table_state = table_state;
   c->params = mlp_params;
@@ -422,6 +455,62 @@ int antdt_bind(antdt_ctx* c, void* tables, float* table_state, float* mlp_params
     for (int l = 0; l <= c->L; ++l) HIP_TRY(c, hipEventCreateWithFlags(&c->ev_dh[l], SYNC_EVENT_FLAGS));
   }
   c->stage = ST_BOUND;
+  return refresh_bf16_weights(c, (hipStream_t)stream);
+}
+
+int antdt_bind_static(antdt_ctx* c, void* tables, float* table_state, float* mlp_params, float* mlp_state,
+                      void* stream) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_bind_static: null context");
+  if (!tables || !table_state || !mlp_params || !mlp_state)
+    return fail(c, ANTDT_INVALID_ARG, "antdt_bind_static: null buffer");
+  if (((uintptr_t)tables & 15) || ((uintptr_t)table_state & 15) || ((uintptr_t)mlp_params & 15) ||
+      ((uintptr_t)mlp_state & 15))
+    return fail(c, ANTDT_INVALID_ARG, "antdt_bind_static: misaligned buffer (16 B)");
+  if (c->ws_bytes > (size_t)ANTDT_STATIC_SCRATCH_BYTES)
+    return fail(c, ANTDT_WORKSPACE_TOO_SMALL,
+                "antdt_bind_static: the model needs " + std::to_string(c->ws_bytes) +
+                    " bytes of scratch, the library's static buffer holds " +
+                    std::to_string((size_t)ANTDT_STATIC_SCRATCH_BYTES) + " (use antdt_bind with a workspace)");
+  int dev = -1;
+  HIP_TRY(c, hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(c, ANTDT_UNSUPPORTED, "antdt_bind_static: device index out of range");
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {  // once per device, with that device current
+      void* p = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return fail(c, ANTDT_HIP_ERROR, std::string("antdt_bind_static: hipGetSymbolAddress: ") + hipGetErrorString(e));
+      g_scratch_ptr[dev] = p;
+    }
+    base = g_scratch_ptr[dev];
+    // The buffer serves one context at a time: the context that held it must be bound again
+    // before its next iteration (its calls fail with BAD_STATE until then).
+    antdt_ctx* prev = g_scratch_owner[dev];
+    if (prev && prev != c) {
+      prev->stage = ST_CREATED;
+      prev->static_bound = false;
+      prev->static_device = -1;
+    }
+    g_scratch_owner[dev] = c;
+  }
+  if (((uintptr_t)base & 255)) return fail(c, ANTDT_HIP_ERROR, "antdt_bind_static: static buffer is not 256-byte aligned");
+  // A context that was bound with antdt_bind before may still have work on its own streams.
+  if (c->side) HIP_TRY(c, hipStreamSynchronize(c->side));
+  if (c->wside) HIP_TRY(c, hipStreamSynchronize(c->wside));
+  c->side_pending = false;
+  c->wgrad_pending = false;
+  c->presorted = false;
+  c->static_bound = true;
+  c->static_device = dev;
+  c->tables = tables;
+  c->table_state = table_state;
+  c->params = mlp_params;
+  c->pstate = mlp_state;
+  carve(c, (char*)base);
+  c->stage = ST_BOUND;
+  c->have_shards = false;
   return refresh_bf16_weights(c, (hipStream_t)stream);
 }
 
@@ -639,7 +728,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     HIP_TRY(c, launch_pool(a, c->fp, s));
   }
   c->presorted = false;
-  if (k0 == 0 && k1 == tab.K && c->side) {
+  if (k0 == 0 && k1 == tab.K && side_stream(c)) {
     // All shards in one pass: the ids and the sample index of every lookup are known now, so
     // the sort and the run detection of the coming aggregate can run beside the MLP.
     for (int k = 0; k < tab.K; ++k) c->included[k] = true;
@@ -714,7 +803,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     // With a weight-gradient stream, only the bias sum and the shard losses stay on the launch
     // stream (one wavefront per shard); the weight sums of the last layer, which nothing needs
     // before the dense update, are computed on that stream ahead of the other weight gradients.
-    c->head_weights_deferred = r.ht != nullptr && L > 1 && c->wside != nullptr;
+    c->head_weights_deferred = r.ht != nullptr && L > 1 && wgrad_stream(c) != nullptr;
     r.part = c->head_weights_deferred ? 2 : 0;
     {
       ProfScope ps(pr, KID_HEAD_REDUCE, s);
@@ -737,7 +826,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
   // Backward.  The data-gradient chain dH_{l+1} -> dH_l stays on the launch stream; the weight
   // gradient of layer l needs dH_{l+1} but nothing needs it before the dense update, so it goes
   // to its own stream and runs beside the rest of the chain and the sparse reduction.
-  hipStream_t ws = c->wside ? c->wside : s;
+  hipStream_t ws = wgrad_stream(c) ? wgrad_stream(c) : s;
   ProfScope bwd_scope(c->act_bf16 && L > 1 ? pr : nullptr, KID_GEMM_BWD, s);
   bwd_scope.launches(L - 1);
   Profiler* pr_each = c->act_bf16 ? nullptr : pr;  // the fp32 path has other kernels in between
@@ -931,7 +1020,7 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
   // The dense update touches nothing the sparse update touches, so it runs on the
   // weight-gradient stream (behind those products, which it needs anyway) beside the sparse
   // update; `s` joins it before this call's work on `s` is complete.
-  hipStream_t ds = c->wside ? c->wside : s;
+  hipStream_t ds = wgrad_stream(c) ? wgrad_stream(c) : s;
   if (ds != s && c->L == 1) {
     // (with hidden layers every worker step ends by making this stream wait for the launch stream)
     HIP_TRY(c, hipEventRecord(c->ev_dh[c->L], s));  // everything enqueued on `s` so far (loss, last layer's gradient)

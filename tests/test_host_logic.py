@@ -69,6 +69,23 @@ def test_create_rejects_bad_layers():
     assert "multiples of 8" in str(e.value)
 
 
+def test_static_binding_checks_its_arguments_before_any_gpu_work():
+    """antdt_bind_static: null or misaligned buffers and a model whose workspace exceeds the
+    library's static buffer are refused on the host, with both sizes in the message."""
+    big = A.Context(A.model_from_config(wl.CONFIGS[2]))
+    assert big.workspace_bytes() > 32 << 20
+    rc = A.lib.antdt_bind_static(big._h, 256, 256, 256, 256, None)
+    msg = A.lib.antdt_last_error(big._h).decode()
+    assert rc == -3 and str(big.workspace_bytes()) in msg and str(32 << 20) in msg
+    small = A.Context(good_model())
+    assert small.workspace_bytes() <= 32 << 20
+    assert A.lib.antdt_bind_static(small._h, None, 256, 256, 256, None) == -1
+    assert A.lib.antdt_bind_static(small._h, 256, 264, 256, 256, None) == -1
+    assert A.lib.antdt_bind_static(None, 256, 256, 256, 256, None) == -1
+    header = open(os.path.join(ROOT, "include", "antdt.h")).read()
+    assert "#define ANTDT_STATIC_SCRATCH_BYTES (32u << 20)" in header
+
+
 def test_call_order_is_checked_before_any_gpu_work():
     ctx = A.Context(good_model())
     assert ctx.workspace_bytes() > 0
