@@ -20,13 +20,17 @@ sparsity, closed forms of the first Adagrad/Adam step, brute-force coalescing
 and brute-force enumeration of Eq. 3 / Eq. 4; for the shard queue its stated
 transitions, at-least-once coverage under random losses and the re-queue order;
 for the job-completion-time model the closed forms of undisturbed, persistently
-disturbed and backup-worker runs, the Eq. 3 split it converges to, and the rate
-of its pseudo-random disturbance pattern.
-Parity unpinned: the paper prints no worked numeric example of an iteration or
-of a schedule, so no pin is a printed value; the decision rules of the
-job-completion-time model beyond those closed forms (window bookkeeping, the
-order of kill and batch-size decisions) are a reading stated in dds_sim.py and
-are pinned only by construction: **parity unpinned** for them.
+disturbed and backup-worker runs, the Eq. 3 split it converges to, the rate of
+its pseudo-random disturbance pattern, and schedules worked out by hand from the
+stated rules (iteration end times, window means, decision iteration, sizes after
+ADJUST_BS, kill time: tests/jct_schedules.py).  The bf16-operand reading of the
+worker step is pinned by a worked example in which every rounding point (stored
+input, operand weights forward and backward, stored activation, gradient after
+the ReLU mask, unrounded biases and last layer) moves a hand-computed result.
+The paper prints no worked numeric example of an iteration or of a schedule, so
+no pin is a printed value.  Parity unpinned: which (window, worker) pairs the
+pseudo-random disturbance pattern picks (only its rate and determinism are
+checked).
 """
 from .ps_iteration import (  # noqa: F401
     Model,

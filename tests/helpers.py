@@ -39,6 +39,20 @@ def oracle_iteration(cfg, tables_f32, state, flat_params, flat_state, batch, siz
     return model, res, agg, upd
 
 
+def permute_batch(batch: wl.Batch, order) -> wl.Batch:
+    """The same samples in another order (bags, dense features and labels move together)."""
+    F = batch.offsets.shape[0]
+    ids, fp, offs = [], [0], np.zeros_like(batch.offsets)
+    for f in range(F):
+        fi, o = batch.field_ids(f), batch.offsets[f]
+        parts = [fi[o[s]:o[s + 1]] for s in order]
+        offs[f, 1:] = np.cumsum([len(p) for p in parts])
+        ids.append(np.concatenate(parts) if parts else fi[:0])
+        fp.append(fp[-1] + int(offs[f, -1]))
+    return wl.Batch(np.concatenate(ids).astype(np.int32), np.array(fp, np.int64), offs,
+                    batch.dense[order], batch.labels[order])
+
+
 def flat_dense_grad(cfg, dW, db):
     out = np.zeros(cfg.num_params, dtype=np.float64)
     for (wo, bo, fi, fo), W, b in zip(wl.param_layout(cfg), dW, db):

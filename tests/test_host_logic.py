@@ -266,6 +266,22 @@ def _same_simulation(**kw):
     return got
 
 
+def _hand_worked():
+    from jct_schedules import SCHEDULES
+    return SCHEDULES
+
+
+@pytest.mark.parametrize("name,cfg,want", _hand_worked(), ids=[s[0] for s in _hand_worked()])
+def test_training_model_follows_hand_worked_schedules(name, cfg, want):
+    """The library's model against schedules worked out by hand (tests/jct_schedules.py): no
+    implementation produced the expected values."""
+    kw = dict(cfg)
+    r, sizes = A.simulate_bsp(**kw)
+    got = dict(jct=r.jct, iterations=r.iterations, processed=r.processed, adjust_actions=r.adjust_actions,
+               kills=r.kills, max_bpt=r.max_bpt, sum_bpt=r.sum_bpt, final_sizes=sizes)
+    assert got == want
+
+
 def test_training_model_matches_the_oracle_for_every_policy():
     rng = np.random.default_rng(23)
     for trial in range(24):

@@ -447,6 +447,51 @@ def test_bf16_gemm_mode_is_exact_on_bf16_representable_integers():
     assert 0 < n < 2e-2
 
 
+def test_bf16_gemm_mode_worked_example_pins_every_rounding_point():
+    """One sample through a 2-3-1 model whose numbers are chosen so that each rounding of the
+    bf16-operand reading changes a result by an amount worked out by hand (bf16 keeps 8
+    significant bits: in [1, 2) the spacing is 2^-7, in [2, 4) it is 2^-6).  Expected values are
+    literals; removing any single rounding from the oracle moves at least one of them.
+
+    pooled input x = [1 + 2^-9, 3]           -> stored as bf16: a0 = [1, 3]
+    W0 = [[1 + 2^-9, 1/2 + 2^-10, -1],       -> as operand:    [[1,   1/2,      -1],
+          [1/4,      1 + 3*2^-9,  -1]]                          [1/4, 1 + 2^-7, -1]]
+    b0 = [2^-8 + 2^-16, 1/8 + 2^-9, 0], added UNROUNDED (as bf16 the first would be 2^-8)
+    pre-activations: [1 + 3/4 + 2^-8 + 2^-16, 1/2 + 3(1 + 2^-7) + 1/8 + 2^-9, -4]
+                   = [1.7539215087890625, 3.650390625, -4]
+    stored activation h = [1.7578125, 3.65625, 0]   (just above the tie 224.5 spacings of 2^-7 -> 225,
+                                                     with a rounded bias it would be the tie -> 224;
+                                                     233.625 spacings of 2^-6 -> 234)
+    last layer on the stored activation with UNROUNDED weights W1 = [2 + 2^-8, 2 + 3*2^-8, 5],
+    b1 = -(225/128 * 513/256 + 117/32 * 515/256) = -356445/32768, so that z = 0 exactly, and with
+    label 0:  loss = ln 2,  dz = sigmoid(0) - 0 = 1/2.
+    backward: dW1 = h * dz = [0.87890625, 1.828125, 0], db1 = 1/2;
+      dz * W1 = [1 + 2^-9, 1 + 3*2^-9, 2.5]; unit 2 did not pass the ReLU; rounded to bf16:
+      dh = [1, 1 + 2^-7, 0];  db0 = dh;  dW0 = a0^T dh = [[1, 1.0078125, 0], [3, 3.0234375, 0]];
+      dx = dh . (rounded W0)^T = [1 + 1.0078125/2, 1/4 + 1.0078125^2] = [1.50390625, 1.26568603515625].
+    """
+    e9, e10, e7, e8 = 2.0 ** -9, 2.0 ** -10, 2.0 ** -7, 2.0 ** -8
+    tables = [np.array([[1.0 + e9]]), np.array([[3.0]])]
+    W0 = np.array([[1.0 + e9, 0.5 + e10, -1.0], [0.25, 1.0 + 3 * e9, -1.0]])
+    b0 = np.array([e8 + 2.0 ** -16, 0.125 + e9, 0.0])
+    W1 = np.array([[2.0 + e8], [2.0 + 3 * e8], [5.0]])
+    b1 = np.array([-356445.0 / 32768.0])
+    batch = wl.Batch(np.zeros(2, np.int32), np.array([0, 1, 2], np.int64), np.array([[0, 1], [0, 1]], np.int32),
+                     np.zeros((1, 0), np.float32), np.zeros(1, np.float32))
+    model = oracle.Model(2, 1, 1, 0, (2, 3, 1), bf16_gemm=True)
+    r = oracle.worker_step(model, tables, [(W0, b0), (W1, b1)], batch, 0, 1)
+    assert np.array_equal(r.acts[0], [[1.0, 3.0]])                       # stored input is rounded
+    assert np.array_equal(r.acts[1], [[1.7578125, 3.65625, 0.0]])       # operand W0 and stored activation rounded, bias not
+    assert r.z[0] == 0.0 and r.loss == math.log(2.0)                    # last layer takes unrounded weights
+    assert np.array_equal(r.dW[1], [[0.87890625], [1.828125], [0.0]]) and np.array_equal(r.db[1], [0.5])
+    assert np.array_equal(r.db[0], [1.0, 1.0 + e7, 0.0])                # dh rounded after the ReLU mask
+    assert np.array_equal(r.dW[0], [[1.0, 1.0078125, 0.0], [3.0, 3.0234375, 0.0]])   # rounded activation times rounded dh
+    assert np.array_equal(r.dx, [[1.50390625, 1.26568603515625]])       # rounded dh through the rounded operand W0
+    # the plain reading of the same numbers differs in every one of these
+    p = oracle.worker_step(oracle.Model(2, 1, 1, 0, (2, 3, 1)), tables, [(W0, b0), (W1, b1)], batch, 0, 1)
+    assert p.z[0] != 0.0 and not np.array_equal(p.dW[0], r.dW[0]) and not np.array_equal(p.dx, r.dx)
+
+
 # ------------------------------------------------------- shard assignment
 def test_eq3_bruteforce_properties():
     from fractions import Fraction
@@ -584,6 +629,21 @@ def test_training_model_closed_forms():
               restart_cost=30.0)
     bsp, lb, nd = _sim(**kw), _sim(policy=D.ADJUST_BS, **kw), _sim(policy=D.ANTDT_ND, **kw)
     assert nd.kills == 1 and nd.jct < 0.3 * bsp.jct and lb.kills == 0 and lb.jct > 0.8 * bsp.jct
+
+
+def _hand_worked():
+    from jct_schedules import SCHEDULES
+    return SCHEDULES
+
+
+@pytest.mark.parametrize("name,cfg,want", _hand_worked(), ids=[s[0] for s in _hand_worked()])
+def test_training_model_follows_hand_worked_schedules(name, cfg, want):
+    """Iteration end times, window means, the decision iteration, the sizes after ADJUST_BS and
+    the kill time of small schedules, worked out by hand in tests/jct_schedules.py."""
+    r = oracle.simulate_bsp(oracle.SimConfig(**cfg))
+    got = dict(jct=r.jct, iterations=r.iterations, processed=r.processed, adjust_actions=r.adjust_actions,
+               kills=r.kills, max_bpt=r.max_bpt, sum_bpt=r.sum_bpt, final_sizes=r.final_sizes)
+    assert got == want
 
 
 def test_transient_pattern_is_deterministic_and_has_the_stated_rate():
