@@ -87,6 +87,7 @@ def _bytes_and_flops(cfg, stats, model):
         "gemm_bwd": ("mfma", dgrad),           # the data-gradient chain on the launch stream
         "gemm_dgrad": ("mfma", dgrad),
         "gemm_wgrad": ("mfma", fwd),
+        "wgrad_adagrad": ("mfma", fwd),    # weight gradients with the aggregation and dense Adagrad in the epilogue
         "sort_hist": ("hbm", passes * 4 * nnz),
         "sort_scatter": ("hbm", 4 * nnz + 8 * nnz + (passes - 1) * 16 * nnz),
         "seg_heads": ("hbm", 4 * nnz),
@@ -382,6 +383,7 @@ def run_batch_sweep(args):
     b = wl.make_batch(cfg, 0)
     ctx = A.Context(A.model_from_config(cfg, max_nnz=int(b.field_ptr[-1])))
     ctx.bind(tables, state, params, pstate)
+    ctx.set_eager_weight_gradients(True)   # a worker's batch time includes its weight gradients
     ctx.set_batch(torch.from_numpy(b.ids).to(dev), b.field_ptr, torch.from_numpy(b.offsets).to(dev),
                   torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.labels).to(dev))
     B = cfg.batch

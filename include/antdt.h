@@ -192,9 +192,10 @@ int antdt_assign_shard(antdt_ctx* ctx, int64_t B, int32_t K, const int64_t* size
  * pair (ids, that gradient) is the shard's sparse gradient.  loss_out: DEVICE fp32 [1], may
  * be NULL.  Requires set_batch and assign_shard with matching B.
  * Everything is enqueued on `stream` except the weight gradients of the hidden layers, which the
- * library computes on a stream of its own beside the rest of the backward pass: they are
- * complete, in the order of `stream`, after antdt_apply_update; antdt_view_shard_grads waits
- * for them on the host.
+ * library computes on a stream of its own, beside the rest of the backward pass or inside
+ * antdt_apply_update (see antdt_set_eager_weight_gradients): the dense parameters are complete, in
+ * the order of `stream`, after antdt_apply_update; antdt_view_shard_grads computes the per-shard
+ * gradients if need be and waits for them on the host.
  */
 int antdt_worker_step(antdt_ctx* ctx, int32_t k, float* loss_out, void* stream);
 
@@ -227,6 +228,19 @@ int antdt_aggregate(antdt_ctx* ctx, const uint8_t* shard_mask, void* stream);
  * Requires antdt_aggregate.
  */
 int antdt_apply_update(antdt_ctx* ctx, void* stream);
+
+/*
+ * Where the weight gradients of the hidden layers are computed.  By default (on == 0), with bf16
+ * matrix products and a context bound by antdt_bind, antdt_worker_step leaves them out:
+ * antdt_apply_update forms them inside the dense update (per shard in registers, weighted and
+ * added up in shard order, then Adagrad; neither the per-shard nor the aggregated gradient is
+ * written), and antdt_view_shard_grads / antdt_view_dense_grad compute the per-shard gradients
+ * on request.  With on != 0 every antdt_worker_step computes its shards' weight gradients itself,
+ * as K separate workers would before pushing them (Section II), and antdt_apply_update
+ * aggregates what they wrote; the results agree to rounding.  Takes effect at the next
+ * antdt_worker_step.  Host only.
+ */
+int antdt_set_eager_weight_gradients(antdt_ctx* ctx, int32_t on);
 
 /*
  * Learning rate of the following antdt_apply_update calls (the ADJUST_LR global action of

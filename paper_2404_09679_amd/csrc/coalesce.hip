@@ -245,8 +245,7 @@ __global__ __launch_bounds__(SORT_THREADS) void seg_heads_kernel(SegArgs a, Fiel
 }
 
 // One block: exclusive prefix over all tiles (-> first unique of every tile and field),
-// the terminal segment offset of every field, the per-sample aggregation weight, and the
-// reset of the two list lengths (long runs, chunks) that seg_queue_kernel counts up.
+// the terminal segment offset of every field and the per-sample aggregation weight.
 __global__ __launch_bounds__(1024) void seg_scan_kernel(SegArgs a, FieldPtr fp, TileBase tb, ShardTab tab) {
   __shared__ int wsum[16];
   const int n = a.total_tiles;
@@ -276,8 +275,6 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(SegArgs a, FieldPtr fp, 
   }
   if (threadIdx.x == 0) {
     a.tile_heads[n] = total;
-    a.counters[0] = 0;
-    a.counters[1] = 0;
     a.segabs[total] = (int32_t)fp.p[a.F];
   }
   __threadfence_block();
@@ -328,18 +325,17 @@ __global__ __launch_bounds__(SORT_THREADS) void seg_emit_kernel(SegArgs a, Field
 
 // Runs longer than the threshold are cut into chunks of `chunk` lookups; the list of such runs
 // and the list of their chunks are built here, beside the run table, so that the reduction
-// kernel finds them ready.  The order of the lists is arbitrary (it does not affect any sum:
-// a run's chunk sums are added in chunk order).
+// kernel finds them ready.  Both lists are in run order (count per block of runs, prefix sum
+// over the blocks, write): consecutive entries belong to the same field, which is what lets the
+// reduction give each of its eight shares a contiguous piece of every list.
 constexpr int QUEUE_RUNS = 8;  // runs per thread
-__global__ __launch_bounds__(256) void seg_queue_kernel(SegArgs a) {
-  __shared__ int wl[4], wc[4], base[2];
-  const int U = a.ubase[a.F];
-  if ((int64_t)blockIdx.x * 256 * QUEUE_RUNS >= U) return;
-  const int64_t u0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * QUEUE_RUNS;
-  // One position in the two lists per block (a returning atomic on one address takes the
-  // memory system some ten nanoseconds: one per long run would make this the longest kernel
-  // of the structure), the places inside the block's share by a prefix sum.
-  int len[QUEUE_RUNS], nl = 0, nc = 0;
+static_assert(256 * QUEUE_RUNS == ANTDT_QUEUE_BLOCK_RUNS, "queue block size");
+constexpr int SHARES = 8;      // one per XCD: blocks are handed to the XCDs round robin
+
+// Long runs and chunks among the block's runs; lengths of the thread's runs in len[].
+__device__ __forceinline__ void queue_count(const SegArgs& a, int U, int64_t u0, int (&len)[QUEUE_RUNS], int& nl, int& nc) {
+  nl = 0;
+  nc = 0;
 #pragma unroll
   for (int i = 0; i < QUEUE_RUNS; ++i) {
     const int64_t u = u0 + i;
@@ -349,6 +345,100 @@ __global__ __launch_bounds__(256) void seg_queue_kernel(SegArgs a) {
       nc += (len[i] + a.chunk - 1) / a.chunk;
     }
   }
+}
+
+__global__ __launch_bounds__(256) void seg_queue_count_kernel(SegArgs a) {
+  __shared__ int wl[4], wc[4];
+  const int U = a.ubase[a.F];
+  const int64_t u0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * QUEUE_RUNS;
+  int len[QUEUE_RUNS], nl, nc;
+  queue_count(a, U, u0, len, nl, nc);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    nl += __shfl_xor(nl, o, 64);
+    nc += __shfl_xor(nc, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    wl[threadIdx.x >> 6] = nl;
+    wc[threadIdx.x >> 6] = nc;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a.qcnt[2 * blockIdx.x] = (wl[0] + wl[1]) + (wl[2] + wl[3]);
+    a.qcnt[2 * blockIdx.x + 1] = (wc[0] + wc[1]) + (wc[2] + wc[3]);
+  }
+}
+
+// One block: exclusive prefix sums of the per-block counts (qcnt[2 * nblocks ..] = the totals),
+// the list lengths, and the table of shares: share x of the reduction owns the runs of the
+// queue blocks [ceil(nq x / 8), ceil(nq (x+1) / 8)), nq = blocks that hold runs, hence a
+// contiguous piece of the run table and of both lists.
+__global__ __launch_bounds__(1024) void seg_queue_scan_kernel(SegArgs a, int nblocks) {
+  __shared__ int wsl[16], wsc[16];
+  const int per = (nblocks + 1023) / 1024;
+  const int lo = min(nblocks, (int)threadIdx.x * per), hi = min(nblocks, lo + per);
+  int sl = 0, sc = 0;
+  for (int i = lo; i < hi; ++i) {
+    sl += a.qcnt[2 * i];
+    sc += a.qcnt[2 * i + 1];
+  }
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int il = sl, ic = sc;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int vl = __shfl_up(il, o, 64), vc = __shfl_up(ic, o, 64);
+    if (lane >= o) {
+      il += vl;
+      ic += vc;
+    }
+  }
+  if (lane == 63) {
+    wsl[w] = il;
+    wsc[w] = ic;
+  }
+  __syncthreads();
+  int bl = il - sl, bc = ic - sc, tl = 0, tc = 0;
+  for (int i = 0; i < 16; ++i) {
+    if (i < w) {
+      bl += wsl[i];
+      bc += wsc[i];
+    }
+    tl += wsl[i];
+    tc += wsc[i];
+  }
+  for (int i = lo; i < hi; ++i) {
+    const int cl = a.qcnt[2 * i], cc = a.qcnt[2 * i + 1];
+    a.qcnt[2 * i] = bl;
+    a.qcnt[2 * i + 1] = bc;
+    bl += cl;
+    bc += cc;
+  }
+  if (threadIdx.x == 0) {
+    a.qcnt[2 * nblocks] = tl;
+    a.qcnt[2 * nblocks + 1] = tc;
+    a.counters[0] = tl;
+    a.counters[1] = tc;
+  }
+  __threadfence_block();
+  __syncthreads();
+  if (threadIdx.x <= SHARES) {
+    const int U = a.ubase[a.F];
+    const int nq = (U + ANTDT_QUEUE_BLOCK_RUNS - 1) / ANTDT_QUEUE_BLOCK_RUNS;  // <= nblocks
+    const int x = threadIdx.x;
+    const int qb = min(nblocks, (int)(((int64_t)nq * x + SHARES - 1) / SHARES));
+    a.xcd_tab[x] = (int)min((int64_t)U, (int64_t)qb * ANTDT_QUEUE_BLOCK_RUNS);
+    a.xcd_tab[9 + x] = a.qcnt[2 * qb + 1];   // first chunk item
+    a.xcd_tab[18 + x] = a.qcnt[2 * qb];      // first long run
+  }
+}
+
+__global__ __launch_bounds__(256) void seg_queue_write_kernel(SegArgs a) {
+  __shared__ int wl[4], wc[4];
+  const int U = a.ubase[a.F];
+  if ((int64_t)blockIdx.x * ANTDT_QUEUE_BLOCK_RUNS >= U) return;
+  const int64_t u0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * QUEUE_RUNS;
+  int len[QUEUE_RUNS], nl, nc;
+  queue_count(a, U, u0, len, nl, nc);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   int il = nl, ic = nc;
 #pragma unroll
@@ -364,13 +454,7 @@ __global__ __launch_bounds__(256) void seg_queue_kernel(SegArgs a) {
     wc[w] = ic;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    const int tl = (wl[0] + wl[1]) + (wl[2] + wl[3]), tc = (wc[0] + wc[1]) + (wc[2] + wc[3]);
-    base[0] = tl ? atomicAdd(&a.counters[0], tl) : 0;
-    base[1] = tc ? atomicAdd(&a.counters[1], tc) : 0;
-  }
-  __syncthreads();
-  int slot = base[0] + il - nl, item = base[1] + ic - nc;
+  int slot = a.qcnt[2 * blockIdx.x] + il - nl, item = a.qcnt[2 * blockIdx.x + 1] + ic - nc;
   for (int i = 0; i < w; ++i) {
     slot += wl[i];
     item += wc[i];
@@ -497,12 +581,12 @@ __device__ __forceinline__ void load_row(const SegArgs& a, int64_t row, int c, f
 // Chunk sums of the long runs.  One block per chunk: the lane groups stride over the chunk, then
 // their partial sums are added in group order (fixed order: repeatable bit for bit).
 template <bool MEAN>
-__device__ __forceinline__ void chunk_sums(const SegArgs& a, int first, int step) {
+__device__ __forceinline__ void chunk_sums(const SegArgs& a, int first, int last, int step) {
   __shared__ float4 red[256];
   const int lps = a.D >> 2;
   const int ngroups = 256 / lps;
   const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
-  const int count = min(a.counters[1], a.item_cap);
+  const int count = min(last, a.item_cap);
   for (int idx = first; idx < count; idx += step) {
     const int u = a.items[idx * 2], q = a.items[idx * 2 + 1];
     const int b = a.segabs[u] + q * a.chunk, e = min(a.segabs[u + 1], b + a.chunk);
@@ -529,18 +613,34 @@ __device__ __forceinline__ void chunk_sums(const SegArgs& a, int first, int step
 // the kernel after this one); the others work one group of D/4 lanes per run: short runs are
 // summed in sorted (= sample) order and, when `UPDATE`, the Adagrad step of the row is applied
 // at once (the coalesced gradient never goes to memory); otherwise the sum is written to G.
+// The work is divided into eight shares of consecutive runs (consecutive runs belong to the same
+// field), and the blocks whose index is x modulo 8, which the hardware places on XCD x, work
+// on share x: the pooled-gradient slice of a field (all samples x D columns) is then fetched into
+// one XCD's L2 instead of all eight.  With fewer than eight blocks there is one share.
 template <typename TT, bool ROWWISE, bool UPDATE, bool MEAN>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a, int chunk_blocks) {
-  if ((int)blockIdx.x < chunk_blocks) {
-    chunk_sums<MEAN>(a, blockIdx.x, chunk_blocks);
+  const int x = blockIdx.x & (SHARES - 1);
+  if ((int)blockIdx.x < chunk_blocks) {  // (chunk_blocks is a multiple of 8)
+    chunk_sums<MEAN>(a, a.xcd_tab[9 + x] + (int)(blockIdx.x >> 3), a.xcd_tab[9 + x + 1], chunk_blocks >> 3);
     return;
   }
   const int64_t bid = (int64_t)blockIdx.x - chunk_blocks, nblk = (int64_t)gridDim.x - chunk_blocks;
   const int lps = a.D >> 2;
-  const int U = a.ubase[a.F];
   const int groups_per_block = 256 / lps;
   const int g = threadIdx.x / lps, c = threadIdx.x - g * lps;
-  for (int64_t u = bid * groups_per_block + g; u < U; u += nblk * groups_per_block) {
+  int64_t lo, hi, slot, nslots;
+  if (nblk >= SHARES) {
+    lo = a.xcd_tab[x];
+    hi = a.xcd_tab[x + 1];
+    slot = bid >> 3;
+    nslots = (nblk - x + SHARES - 1) >> 3;
+  } else {
+    lo = 0;
+    hi = a.ubase[a.F];
+    slot = bid;
+    nslots = nblk;
+  }
+  for (int64_t u = lo + slot * groups_per_block + g; u < hi; u += nslots * groups_per_block) {
     const int b = a.segabs[u], e = a.segabs[u + 1];
     if (e - b > a.long_threshold) continue;
     const int f = a.ufield[u];
@@ -651,9 +751,14 @@ hipError_t launch_segments(const SegArgs& a, const FieldPtr& fp, const TileBase&
   if (a.total_tiles > 0) {
     ProfScope ps(prof, KID_SEG_EMIT, s);
     hipLaunchKernelGGL(seg_emit_kernel, grid, dim3(SORT_THREADS), 0, s, a, fp, tb);
+  }
+  {  // lists of the long runs and their chunks, and the table of shares (also when there is no lookup)
     const int64_t nnz = fp.p[a.F];
-    const unsigned qb = (unsigned)((nnz + 256 * QUEUE_RUNS - 1) / (256 * QUEUE_RUNS));  // runs <= lookups
-    hipLaunchKernelGGL(seg_queue_kernel, dim3(qb), dim3(256), 0, s, a);
+    const unsigned qb = (unsigned)((nnz + ANTDT_QUEUE_BLOCK_RUNS - 1) / ANTDT_QUEUE_BLOCK_RUNS);  // runs <= lookups
+    ProfScope ps(prof, KID_SEG_EMIT, s);
+    if (qb) hipLaunchKernelGGL(seg_queue_count_kernel, dim3(qb), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(seg_queue_scan_kernel, dim3(1), dim3(1024), 0, s, a, (int)qb);
+    if (qb) hipLaunchKernelGGL(seg_queue_write_kernel, dim3(qb), dim3(256), 0, s, a);
   }
   return hipGetLastError();
 }
@@ -672,6 +777,7 @@ hipError_t launch_seg_reduce(const SegArgs& a, int64_t nnz_total, Profiler* prof
   const int groups_per_block = 256 / (a.D >> 2);
   int64_t nb = (nnz_total + groups_per_block - 1) / groups_per_block;
   if (nb > 256 * 32) nb = 256 * 32;
+  if (nb >= SHARES) nb = (nb + SHARES - 1) / SHARES * SHARES;   // the same number of blocks for every share
   const unsigned blocks = (unsigned)nb;
   // one lane group per long run; there are at most nnz / threshold of them (blocks past the
   // actual number leave at once)

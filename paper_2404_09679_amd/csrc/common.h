@@ -68,6 +68,7 @@ enum KernelId {
   KID_ADAM,
   KID_TRANSPOSE,
   KID_GEMM_BWD,
+  KID_WGRAD_ADAGRAD,
   KID_COUNT
 };
 
@@ -145,6 +146,32 @@ struct GemmArgs {
 };
 hipError_t launch_gemm(const GemmArgs& a, const ShardTab& tab, hipStream_t s);
 
+// Weight gradients of all hidden layers with the server's aggregation and dense update applied
+// on the spot: for layer l the tile of [dW_l ; db_l] = sum_k w_k * ([act_l ; 1]^T dH_{l+1}) over
+// the samples of shard k, accumulated shard after shard in registers, then Adagrad on the matching
+// tile of the flat parameters (W_l with b_l right behind it) and the bf16 copy of W_l.  Neither
+// the per-shard nor the aggregated gradient goes to memory.
+struct KSegments {        // sample ranges with one aggregation weight each (shards; neighbours of
+  int32_t n;              // equal weight merged), in sample order
+  int32_t ks[ANTDT_MAX_SHARDS], ke[ANTDT_MAX_SHARDS];
+  float w[ANTDT_MAX_SHARDS];
+};
+struct WgradUpdateArgs {
+  int32_t n_layers;
+  const bf16_t* A[ANTDT_MAX_LAYERS];   // transposed activations [M (with the ones row), ld]
+  const bf16_t* B[ANTDT_MAX_LAYERS];   // transposed pre-activation gradients [N, ld]
+  int32_t M[ANTDT_MAX_LAYERS], N[ANTDT_MAX_LAYERS];
+  int64_t w_off[ANTDT_MAX_LAYERS];     // W_l inside the flat parameters, [M - 1, N] then the bias [N]
+  bf16_t* wb[ANTDT_MAX_LAYERS];        // bf16 copy of W_l, [rows padded, N]
+  int32_t tile_base[ANTDT_MAX_LAYERS + 1];
+  int32_t tiles_n[ANTDT_MAX_LAYERS];
+  int64_t ld;
+  float* p;
+  float* state;
+  float lr, eps;
+};
+hipError_t launch_wgrad_update(const WgradUpdateArgs& a, const KSegments& seg, hipStream_t s);
+
 struct CastArgs {  // fp32 [rows, cols] -> bf16 [rows_pad, cols], extra rows zero
   const float* src;
   bf16_t* dst;
@@ -211,6 +238,8 @@ hipError_t launch_bias_grad(const BiasGradArgs& a, const ShardTab& tab, hipStrea
 // ------------------------------------------------------------- coalesce.hip
 // Keys per sort tile (one block of 512 threads, ANTDT_SORT_TILE / 512 keys per thread).
 constexpr int ANTDT_SORT_TILE = 2048;
+// Runs per block of the kernels that list the long runs (256 threads, 8 runs each).
+constexpr int ANTDT_QUEUE_BLOCK_RUNS = 2048;
 
 struct SortPlan {
   int32_t F, B;
@@ -241,6 +270,10 @@ struct SegArgs {
   int32_t* segoff;                 // [U + F], per-field offsets; field f's slice starts at ubase[f] + f
   float* sample_w;                 // [B]
   int32_t* counters;               // [2]: number of long runs, number of chunk work items
+  int32_t* qcnt;                   // [2 * queue blocks]: long runs and chunks found by each block of the list
+                                   // builder, then their exclusive prefix sums
+  int32_t* xcd_tab;                // [3][9]: first run, first chunk item and first long run of each of the 8
+                                   // shares into which the reduction divides its work (entry 8 = the totals)
   int32_t* long_seg;               // [long_cap][3]: run, first item, number of chunks
   int32_t* items;                  // [item_cap][2]: run, chunk index
   float* partial;                  // [item_cap, D] chunk sums of long runs

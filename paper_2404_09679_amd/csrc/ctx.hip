@@ -6,6 +6,7 @@
 
 #include <mutex>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "common.h"
@@ -66,7 +67,7 @@ static const char* kKernelNames[KID_COUNT] = {
     "pool",        "gemm_fwd",   "gemm_dgrad",     "gemm_wgrad",  "head",
     "head_reduce", "bias_grad",  "sort_hist",      "sort_scan",   "sort_scatter",
     "seg_heads",   "seg_scan",   "seg_emit",       "seg_reduce",  "seg_reduce_long",
-    "dense_agg",   "sparse_adagrad", "dense_adagrad", "adam", "transpose", "gemm_bwd"};
+    "dense_agg",   "sparse_adagrad", "dense_adagrad", "adam", "transpose", "gemm_bwd", "wgrad_adagrad"};
 
 }  // namespace antdt
 
@@ -112,13 +113,15 @@ struct antdt_ctx {
   float *z = nullptr, *loss_s = nullptr, *dz = nullptr, *loss_k = nullptr, *dx = nullptr;
   float *shard_grads = nullptr, *g_dense = nullptr, *sample_w = nullptr, *G = nullptr;
   bf16_t* wb[ANTDT_MAX_LAYERS] = {};     // bf16 W_l as [in (padded), out]: operand of the data gradient
+  bf16_t* wb0_alt = nullptr;             // second buffer for W_0: the fused dense update writes the new copy there
+                                         // while the input-gradient product may still read the old one
   bf16_t* wbt[ANTDT_MAX_LAYERS] = {};    // bf16 W_l^T as [out, in (padded)]: operand of the forward product
   bf16_t* act_t[ANTDT_MAX_LAYERS] = {};  // transposed activations [width + 8, ldt], row `width` = ones
   bf16_t* dh_t[ANTDT_MAX_LAYERS] = {};   // transposed pre-activation gradients [width, ldt]
   int64_t ldt = 0;
   int32_t* lookup_sample = nullptr;
   int32_t *key[2] = {}, *pay[2] = {}, *tile_heads = nullptr, *ubase = nullptr, *uniq = nullptr;
-  int32_t *segoff = nullptr, *ufield = nullptr, *segabs = nullptr, *counters = nullptr, *long_seg = nullptr, *items = nullptr;
+  int32_t *segoff = nullptr, *ufield = nullptr, *segabs = nullptr, *counters = nullptr, *long_seg = nullptr, *items = nullptr, *qcnt = nullptr, *xcd_tab = nullptr;
   float* partial = nullptr;
   uint32_t *hist = nullptr, *digit_base = nullptr;
   // batch
@@ -146,6 +149,12 @@ struct antdt_ctx {
   double shard_scale[ANTDT_MAX_SHARDS];  // per-worker factor on the aggregation weight (1 unless set)
   bool weights_dirty = false;            // the factors changed after the weights were last formed
   bool head_weights_deferred = false;    // the last layer's weight sums of this worker step are still to be launched
+  // Weight gradients formed inside the dense update (bf16 products with a weight-gradient stream):
+  // the worker step only leaves their operands behind and an event (ev_dh[0]) that says they are
+  // complete; per-shard gradients are computed when a view asks for them.
+  bool eager_wgrad = false;              // option: the worker step computes the per-shard weight gradients itself
+  bool wgrad_deferred = false;           // this worker step left the weight gradients to apply_update / the views
+  bool shard_grads_done = false;         // the per-shard dense gradients of this worker step are (being) written
   HeadReduceArgs head_reduce_args;
   int sorted_buf = 0;
   // side stream on which the coalescing structure of a batch is built while the MLP runs
@@ -219,6 +228,7 @@ static size_t carve(antdt_ctx* c, char* base) {
     for (int l = 0; l + 1 < c->L; ++l) {
       const int64_t rows = l == 0 ? c->ldx : c->width[l];
       c->wb[l] = (bf16_t*)take((size_t)rows * c->width[l + 1] * 2);
+      if (l == 0) c->wb0_alt = (bf16_t*)take((size_t)rows * c->width[l + 1] * 2);
       c->wbt[l] = (bf16_t*)take((size_t)rows * c->width[l + 1] * 2);
     }
     for (int l = 0; l < c->L; ++l) {
@@ -241,6 +251,8 @@ static size_t carve(antdt_ctx* c, char* base) {
   c->ufield = (int32_t*)take((size_t)N * 4);
   c->segabs = (int32_t*)take((size_t)(N + 1) * 4);
   c->counters = (int32_t*)take(8);
+  c->qcnt = (int32_t*)take((size_t)(N / ANTDT_QUEUE_BLOCK_RUNS + 2) * 8);
+  c->xcd_tab = (int32_t*)take(3 * 9 * 4);
   c->cbase = (int64_t*)take((size_t)(ANTDT_MAX_FIELDS + 1) * 8);
   c->vflags = (int32_t*)take(8);
   c->long_seg = (int32_t*)take((size_t)c->long_cap * 12);
@@ -415,6 +427,10 @@ static int refresh_bf16_weights(antdt_ctx* c, hipStream_t s) {
     a.n_src = (int64_t)c->width[l] * c->width[l + 1];
     a.n_dst = (int64_t)(l == 0 ? c->ldx : c->width[l]) * c->width[l + 1];
     HIP_TRY(c, launch_cast_bf16(a, s));
+    if (l == 0) {  // (its padding rows must be zero as well)
+      a.dst = c->wb0_alt;
+      HIP_TRY(c, launch_cast_bf16(a, s));
+    }
   }
   // constant rows of the transposed activations: a row of ones below the last feature row
   // (it turns the bias gradient into one more row of the weight-gradient product), zeros after
@@ -651,7 +667,7 @@ static void fill_seg_args(antdt_ctx* c, SegArgs& a) {
   memset(&a, 0, sizeof(a));
   a.key = c->key[c->sorted_buf]; a.pay = c->pay[c->sorted_buf];
   a.tile_heads = c->tile_heads; a.ubase = c->ubase; a.uniq = c->uniq; a.ufield = c->ufield;
-  a.segabs = c->segabs; a.segoff = c->segoff; a.sample_w = c->sample_w; a.counters = c->counters;
+  a.segabs = c->segabs; a.segoff = c->segoff; a.sample_w = c->sample_w; a.counters = c->counters; a.qcnt = c->qcnt; a.xcd_tab = c->xcd_tab;
   a.long_seg = c->long_seg; a.items = c->items; a.partial = c->partial;
   a.G = c->G; a.dx = c->dx; a.lddx = c->FD;
   a.offsets = c->offsets; a.mean_pool = m.pooling == ANTDT_POOL_MEAN;
@@ -692,6 +708,59 @@ static int build_coalescing(antdt_ctx* c, const int32_t* ids, const int32_t* pay
   SegArgs a;
   fill_seg_args(c, a);
   HIP_TRY(c, launch_segments(a, c->afp, c->atb, c->tab, pr, s));
+  return ANTDT_OK;
+}
+
+// Per-shard weight gradient of hidden layer l for shards [k0, k1), one grouped product on `ws`.
+static int shard_weight_gradient(antdt_ctx* c, int l, int k0, int k1, hipStream_t ws) {
+  Profiler* pr = prof_of(c);
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  if (c->act_bf16) {
+    // [dW_l ; db_l][k] = [act_l ; 1]^T dh_{l+1} over the shard's samples: both operands are the
+    // transposed copies (sample index contiguous); the ones row yields the bias gradient,
+    // which sits right behind W_l in the flat layout.
+    g.A = c->act_t[l]; g.lda = c->ldt;
+    g.B = c->dh_t[l + 1]; g.ldb = c->ldt;
+    g.M = c->width[l] + 1;
+    g.bf16_in = 1;
+  } else {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
+    g.A = l == 0 ? c->x : c->h[l]; g.lda = l == 0 ? c->ldx : c->width[l]; g.a_kc = 0;
+    g.B = c->dh[l + 1]; g.ldb = c->width[l + 1]; g.b_kc = 0;
+    g.M = c->width[l];
+    g.bf16_in = 0;
+  }
+  g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
+  g.N = c->width[l + 1]; g.K = 0;
+  g.epi = EPI_PLAIN; g.bf16_out = 0;
+  g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
+  ProfScope ps(pr, KID_GEMM_WGRAD, ws);
+  HIP_TRY(c, launch_gemm(g, c->tab, ws));
+  return ANTDT_OK;
+}
+
+// The per-shard dense gradients of a worker step that left them to the dense update: computed
+// now, on the weight-gradient stream, for a view (or the stand-alone aggregation) that wants
+// them in memory.  Shards that were not stepped get whatever their rows hold (never read back).
+static int compute_shard_grads(antdt_ctx* c) {
+  if (!c->wgrad_deferred || c->shard_grads_done) return ANTDT_OK;
+  hipStream_t ws = c->wside;
+  HIP_TRY(c, hipStreamWaitEvent(ws, c->ev_dh[0], 0));
+  {
+    HeadReduceArgs r = c->head_reduce_args;
+    r.part = 1;
+    r.k_begin = 0; r.k_end = c->tab.K;
+    r.loss_out = nullptr;
+    ProfScope ps(prof_of(c), KID_HEAD_REDUCE, ws);
+    HIP_TRY(c, launch_head_reduce(r, c->tab, ws));
+  }
+  for (int l = c->L - 2; l >= 0; --l) {
+    const int rc = shard_weight_gradient(c, l, 0, c->tab.K, ws);
+    if (rc) return rc;
+  }
+  HIP_TRY(c, hipEventRecord(c->ev_wgrad, ws));
+  c->wgrad_pending = true;
+  c->shard_grads_done = true;
   return ANTDT_OK;
 }
 
@@ -803,7 +872,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     // With a weight-gradient stream, only the bias sum and the shard losses stay on the launch
     // stream (one wavefront per shard); the weight sums of the last layer, which nothing needs
     // before the dense update, are computed on that stream ahead of the other weight gradients.
-    c->head_weights_deferred = r.ht != nullptr && L > 1 && wgrad_stream(c) != nullptr;
+    c->head_weights_deferred = r.ht != nullptr && L > 1 && wgrad_stream(c) != nullptr;  // (launched with the weight gradients)
     r.part = c->head_weights_deferred ? 2 : 0;
     {
       ProfScope ps(pr, KID_HEAD_REDUCE, s);
@@ -827,38 +896,18 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
   // gradient of layer l needs dH_{l+1} but nothing needs it before the dense update, so it goes
   // to its own stream and runs beside the rest of the chain and the sparse reduction.
   hipStream_t ws = wgrad_stream(c) ? wgrad_stream(c) : s;
+  // With bf16 products and a weight-gradient stream the weight gradients are not computed here
+  // at all: apply_update forms them inside the dense update (aggregated over the shards in
+  // registers, never written per shard), and this step only records when their operands are
+  // complete.  The per-shard gradients of the contract are computed when a view asks for them.
+  const bool deferred = c->act_bf16 && L > 1 && ws != s && !c->eager_wgrad;
+  c->wgrad_deferred = deferred;
+  c->shard_grads_done = false;
+  if (deferred && L == 2) HIP_TRY(c, hipEventRecord(c->ev_dh[0], s));  // dH_1 comes from the loss kernel
   ProfScope bwd_scope(c->act_bf16 && L > 1 ? pr : nullptr, KID_GEMM_BWD, s);
   bwd_scope.launches(L - 1);
   Profiler* pr_each = c->act_bf16 ? nullptr : pr;  // the fp32 path has other kernels in between
-  auto weight_gradient = [&](int l) -> int {
-    if (c->act_bf16) {
-      // [dW_l ; db_l][k] = [act_l ; 1]^T dh_{l+1} over the shard's samples: both operands are the
-      // transposed copies (sample index contiguous); the ones row yields the bias gradient,
-      // which sits right behind W_l in the flat layout.
-      GemmArgs g;
-      memset(&g, 0, sizeof(g));
-      g.A = c->act_t[l]; g.lda = c->ldt;
-      g.B = c->dh_t[l + 1]; g.ldb = c->ldt;
-      g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
-      g.M = c->width[l] + 1; g.N = c->width[l + 1]; g.K = 0;
-      g.epi = EPI_PLAIN; g.bf16_in = 1; g.bf16_out = 0;
-      g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
-      ProfScope ps(pr, KID_GEMM_WGRAD, ws);
-      HIP_TRY(c, launch_gemm(g, tab, ws));
-    } else {  // dW_l[k] = act_l^T dh_{l+1} over the shard's samples
-      GemmArgs g;
-      memset(&g, 0, sizeof(g));
-      g.A = act(l); g.lda = ld(l); g.a_kc = 0;
-      g.B = c->dh[l + 1]; g.ldb = c->width[l + 1]; g.b_kc = 0;
-      g.C = c->shard_grads + c->w_off[l]; g.ldc = c->width[l + 1];
-      g.M = c->width[l]; g.N = c->width[l + 1]; g.K = 0;
-      g.epi = EPI_PLAIN; g.bf16_in = 0; g.bf16_out = 0;
-      g.grouped = 1; g.k0 = k0; g.groups = k1 - k0; g.group_stride = c->Pstride;
-      ProfScope ps(pr, KID_GEMM_WGRAD, ws);
-      HIP_TRY(c, launch_gemm(g, tab, ws));
-    }
-    return ANTDT_OK;
-  };
+  auto weight_gradient = [&](int l) -> int { return shard_weight_gradient(c, l, k0, k1, ws); };
   // An event record costs the launch stream about as much as a small kernel, so the weight
   // gradients are released in pairs: after the data gradient of layer l both dW_l (needs
   // dH_{l+1}) and dW_{l-1} (needs dH_l) can start.
@@ -893,6 +942,10 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
       ProfScope ps(pr_each, KID_GEMM_DGRAD, s);
       HIP_TRY(c, launch_gemm(g, tab, s));
     }
+    if (deferred) {
+      if (l == 1) HIP_TRY(c, hipEventRecord(c->ev_dh[0], s));  // dH_1, the last operand of the weight gradients
+      continue;
+    }
     const bool release = l == 0 || ((L - 2 - l) & 1) == 0;
     if (release) {
       if (ws != s) {
@@ -914,7 +967,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
     }
   }
   bwd_scope.close();
-  if (L > 1 && ws != s) {
+  if (L > 1 && ws != s && !deferred) {
     HIP_TRY(c, hipEventRecord(c->ev_wgrad, ws));
     c->wgrad_pending = true;
   }
@@ -1004,6 +1057,12 @@ int antdt_set_shard_scale(antdt_ctx* c, const double* scale, int32_t K) {
   return ANTDT_OK;
 }
 
+int antdt_set_eager_weight_gradients(antdt_ctx* c, int32_t on) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_eager_weight_gradients: null context");
+  c->eager_wgrad = on != 0;
+  return ANTDT_OK;
+}
+
 int antdt_set_lr(antdt_ctx* c, float lr) {
   if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_lr: null context");
   if (!(lr >= 0.f) || !isfinite(lr)) return fail(c, ANTDT_INVALID_ARG, "antdt_set_lr: lr must be finite and >= 0");
@@ -1032,7 +1091,69 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
     a.update = 1;
     HIP_TRY(c, launch_seg_reduce(a, c->afp.p[m.num_fields], pr, s));
   }
-  {
+  if (c->wgrad_deferred) {
+    // Weight gradients, their aggregation over the shards and the dense update in one kernel
+    // (the per-shard and the aggregated gradient stay in registers), behind the event that
+    // says the worker step's activations and pre-activation gradients are complete.
+    HIP_TRY(c, hipStreamWaitEvent(ds, c->ev_dh[0], 0));
+    const int Lh = c->L - 1;  // hidden layers
+    if (!c->shard_grads_done) {  // last layer: per-shard weight sums (its bias sum is already there)
+      HeadReduceArgs r = c->head_reduce_args;
+      r.part = 1;
+      r.k_begin = 0; r.k_end = c->tab.K;
+      r.loss_out = nullptr;
+      ProfScope ps(pr, KID_HEAD_REDUCE, ds);
+      HIP_TRY(c, launch_head_reduce(r, c->tab, ds));
+    }
+    {
+      DenseAdagradArgs a;  // plain range: the last layer's weights and bias
+      memset(&a, 0, sizeof(a));
+      a.p = c->params; a.state = c->pstate; a.grads = c->shard_grads; a.stride = c->Pstride; a.lr = m.lr; a.eps = m.eps;
+      a.n_mat = 0; a.n_rng = 1;
+      a.rng_off[0] = c->w_off[Lh]; a.rng_len[0] = c->P - c->w_off[Lh];
+      a.rng_block[0] = 0; a.rng_block[1] = (int)((a.rng_len[0] + 255) / 256);
+      ProfScope ps(pr, KID_DENSE_ADAGRAD, ds);
+      HIP_TRY(c, launch_dense_adagrad(a, c->tab, ds));
+    }
+    WgradUpdateArgs u;
+    memset(&u, 0, sizeof(u));
+    u.n_layers = Lh;
+    for (int l = 0; l < Lh; ++l) {
+      u.A[l] = c->act_t[l]; u.B[l] = c->dh_t[l + 1];
+      u.M[l] = c->width[l] + 1; u.N[l] = c->width[l + 1];
+      u.w_off[l] = c->w_off[l]; u.wb[l] = l == 0 ? c->wb0_alt : c->wb[l];
+    }
+    u.ld = c->ldt; u.p = c->params; u.state = c->pstate; u.lr = m.lr; u.eps = m.eps;
+    KSegments seg;
+    memset(&seg, 0, sizeof(seg));
+    for (int k = 0; k < c->tab.K; ++k) {
+      const float w = c->tab.w[k];
+      if (w == 0.0f || c->tab.len[k] == 0) continue;
+      const int ks = c->tab.start[k], ke = ks + c->tab.len[k];
+      if (seg.n > 0 && seg.w[seg.n - 1] == w && seg.ke[seg.n - 1] == ks) {
+        seg.ke[seg.n - 1] = ke;  // neighbours of equal weight: one range
+      } else {
+        seg.ks[seg.n] = ks; seg.ke[seg.n] = ke; seg.w[seg.n] = w;
+        ++seg.n;
+      }
+    }
+    {
+      ProfScope ps(pr, KID_WGRAD_ADAGRAD, ds);
+      HIP_TRY(c, launch_wgrad_update(u, seg, ds));
+    }
+    // The input-gradient product of this step, enqueued behind the event this stream waited for,
+    // may still be reading the old bf16 copy of W_0: the kernel wrote the new one to the other
+    // buffer, which is the current one from here on (the products of deeper layers ran before
+    // the event).
+    std::swap(c->wb[0], c->wb0_alt);
+    {
+      const int rc = transpose_weights(c, ds);  // the forward operand copies W_l^T from the new W_l
+      if (rc) return rc;
+    }
+    HIP_TRY(c, hipEventRecord(c->ev_wgrad, ds));
+    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_wgrad, 0));
+    c->wgrad_pending = false;  // `s` now waits for everything on that stream
+  } else {
     DenseAdagradArgs a;
     memset(&a, 0, sizeof(a));
     a.p = c->params; a.state = c->pstate; a.grads = c->shard_grads; a.stride = c->Pstride; a.lr = m.lr; a.eps = m.eps;
@@ -1127,6 +1248,10 @@ int antdt_view_shard_grads(antdt_ctx* c, int32_t k, const float** dense, const f
   if (!c || !dense || !dx || !ld_dx) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: null argument");
   if (!c->have_shards || k < 0 || k >= c->tab.K) return fail(c, ANTDT_INVALID_ARG, "antdt_view_shard_grads: shard index out of range");
   if (c->stage < ST_BATCH) return fail(c, ANTDT_BAD_STATE, "antdt_view_shard_grads: nothing computed yet");
+  {
+    const int rcg = compute_shard_grads(c);
+    if (rcg) return rcg;
+  }
   if (c->wgrad_pending) {  // the weight gradients are written on their own stream: wait for it here
     HIP_TRY(c, hipStreamSynchronize(c->wside));
     c->wgrad_pending = false;
@@ -1141,6 +1266,8 @@ int antdt_view_dense_grad(antdt_ctx* c, const float** g, void* stream) {
   if (!c || !g) return fail(c, ANTDT_INVALID_ARG, "antdt_view_dense_grad: null argument");
   if (c->stage != ST_AGGREGATED) return fail(c, ANTDT_BAD_STATE, "antdt_view_dense_grad: valid between antdt_aggregate and antdt_apply_update");
   {
+    const int rcg = compute_shard_grads(c);
+    if (rcg) return rcg;
     const int rcj = join_wgrad(c, (hipStream_t)stream);
     if (rcj) return rcj;
   }

@@ -48,34 +48,20 @@ __device__ __forceinline__ uint32_t relu_mask2(uint32_t v, uint32_t mk) {
   return v & (lo | hi);
 }
 
-// C[m, n] = sum_{k in [ks, ke)} A[m*lda + k] * B[n*ldb + k].
+// acc[i][j] += sum_{k in [ks, ke)} A[m*lda + k] * B[n*ldb + k] for the block tile at (m0, n0).
 // Block tile (32*TM*WR) x (32*TN*WC): WR x WC wavefronts, each TM x TN MFMA tiles of 32x32.
-// Global -> registers -> LDS with the next tile's loads in flight during the MFMAs.
-// Blocks are numbered so that the blocks sharing an A row-panel run on the same XCD (L2).
-template <int TM, int TN, int WR, int WC, bool GROUPED>
-__global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, ShardTab tab, int tiles_m, int tiles_n) {
+// Global -> registers -> LDS with the next tile's loads in flight during the MFMAs.  CLIP: the
+// range need not start or end on a multiple of 8 (a shard's samples): the elements of the first
+// and last 16-byte vectors that lie outside it are zeroed.  On return every wavefront has
+// passed the last barrier: the LDS tiles are free.
+template <int TM, int TN, int WR, int WC, bool CLIP>
+__device__ __forceinline__ void accumulate_k(const bf16_t* A, const bf16_t* B, int64_t lda, int64_t ldb, int M, int N,
+                                             int m0, int n0, int ks, int ke, bf16_t* la, bf16_t* lb,
+                                             f32x16 (&acc)[TM][TN]) {
   constexpr int THREADS = 64 * WR * WC;
   constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
   constexpr int VA = BM * BK / 8 / THREADS, VB = BN * BK / 8 / THREADS;  // 16-byte vectors per thread
   static_assert(VA >= 1 && VB >= 1 && VA * THREADS * 8 == BM * BK && VB * THREADS * 8 == BN * BK, "tile / thread count");
-  __shared__ __attribute__((aligned(16))) bf16_t lds[(BM + BN) * PITCH];
-  bf16_t* la = lds;
-  bf16_t* lb = lds + BM * PITCH;
-
-  const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
-  const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
-  char* C = reinterpret_cast<char*>(p.C);
-  int ks = 0, ke = p.K;
-  if (GROUPED) {
-    const int k = p.k0 + blockIdx.z;
-    ks = tab.start[k];
-    ke = ks + tab.len[k];
-    C += (int64_t)k * p.group_stride * (p.bf16_out ? 2 : 4);
-  }
-  int pid = blockIdx.x;
-  const int nblk = tiles_m * tiles_n;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / WC, wc = wave % WC;
   const int fr = lane & 31, fg = lane >> 5;
@@ -93,45 +79,36 @@ __global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, Sha
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
       const int v = tid + i * THREADS;
-      const int row = min(m0 + (v >> 3), p.M - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
-      ra[i] = *reinterpret_cast<const uint4*>(A + (int64_t)row * p.lda + k);
+      const int row = min(m0 + (v >> 3), M - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
+      ra[i] = *reinterpret_cast<const uint4*>(A + (int64_t)row * lda + k);
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
       const int v = tid + i * THREADS;
-      const int row = min(n0 + (v >> 3), p.N - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
-      rb[i] = *reinterpret_cast<const uint4*>(B + (int64_t)row * p.ldb + k);
+      const int row = min(n0 + (v >> 3), N - 1), k = min(kfirst + kt * BK + (v & 7) * 8, klast);
+      rb[i] = *reinterpret_cast<const uint4*>(B + (int64_t)row * ldb + k);
     }
   };
   // straight-line code only: a branch here makes the compiler wait for every outstanding load
   auto fix = [&](uint4 val, bool row_ok, int k) -> uint4 {
     const uint32_t all = (row_ok && k < ke) ? 0xFFFFFFFFu : 0u;
-    if (GROUPED) return clip_k(val, k, ks, ke, all);
+    if (CLIP) return clip_k(val, k, ks, ke, all);
     return make_uint4(val.x & all, val.y & all, val.z & all, val.w & all);
   };
   auto store_tile = [&](int kt, const uint4 (&ra)[VA], const uint4 (&rb)[VB]) {
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
       const int v = tid + i * THREADS;
-      const uint4 val = fix(ra[i], m0 + (v >> 3) < p.M, kfirst + kt * BK + (v & 7) * 8);
+      const uint4 val = fix(ra[i], m0 + (v >> 3) < M, kfirst + kt * BK + (v & 7) * 8);
       *reinterpret_cast<uint4*>(la + (v >> 3) * PITCH + (v & 7) * 8) = val;
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
       const int v = tid + i * THREADS;
-      const uint4 val = fix(rb[i], n0 + (v >> 3) < p.N, kfirst + kt * BK + (v & 7) * 8);
+      const uint4 val = fix(rb[i], n0 + (v >> 3) < N, kfirst + kt * BK + (v & 7) * 8);
       *reinterpret_cast<uint4*>(lb + (v >> 3) * PITCH + (v & 7) * 8) = val;
     }
   };
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
   auto multiply = [&]() {
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
@@ -171,6 +148,43 @@ __global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, Sha
     multiply();
     __syncthreads();
   }
+}
+
+// C[m, n] = sum_{k in [ks, ke)} A[m*lda + k] * B[n*ldb + k], with the epilogue of GemmArgs.
+// Blocks are numbered so that the blocks sharing an A row-panel run on the same XCD (L2).
+template <int TM, int TN, int WR, int WC, bool GROUPED>
+__global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, ShardTab tab, int tiles_m, int tiles_n) {
+  constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[(BM + BN) * PITCH];
+  bf16_t* la = lds;
+  bf16_t* lb = lds + BM * PITCH;
+
+  const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
+  const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
+  char* C = reinterpret_cast<char*>(p.C);
+  int ks = 0, ke = p.K;
+  if (GROUPED) {
+    const int k = p.k0 + blockIdx.z;
+    ks = tab.start[k];
+    ke = ks + tab.len[k];
+    C += (int64_t)k * p.group_stride * (p.bf16_out ? 2 : 4);
+  }
+  int pid = blockIdx.x;
+  const int nblk = tiles_m * tiles_n;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / WC, wc = wave % WC;
+  const int fr = lane & 31, fg = lane >> 5;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  accumulate_k<TM, TN, WR, WC, GROUPED>(A, B, p.lda, p.ldb, p.M, p.N, m0, n0, ks, ke, la, lb, acc);
 
   // Epilogue.  In the D fragment lane (fr, fg) holds column fr and rows 8*(v/4) + 4*fg + v%4
   // (v = 0..15) of each 32x32 tile, which would mean 2-byte scattered stores.  Each wavefront instead stages its
@@ -287,6 +301,102 @@ __global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, Sha
             if (n + 3 < p.N) dst[3] = val.w;
           }
         }
+      }
+    }
+  }
+}
+
+// Weight gradient + aggregation + dense Adagrad of one tile (see WgradUpdateArgs).  The sums of
+// the sample ranges are formed one after the other, each from zero, and added up with their
+// weights in range order: g = fma(w_k, sum_k, g), the order in which the stand-alone dense
+// update adds the shards' gradients.
+template <int TM, int TN, int WR, int WC>
+__global__ __launch_bounds__(64 * WR * WC) void wgrad_update_kernel(WgradUpdateArgs u, KSegments seg) {
+  constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[(BM + BN) * PITCH];
+  bf16_t* la = lds;
+  bf16_t* lb = lds + BM * PITCH;
+  int li = 0;
+  while (li + 1 < u.n_layers && (int)blockIdx.x >= u.tile_base[li + 1]) ++li;
+  const int pid = blockIdx.x - u.tile_base[li];
+  const int M = u.M[li], N = u.N[li];
+  const int m0 = (pid / u.tiles_n[li]) * BM, n0 = (pid % u.tiles_n[li]) * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / WC, wc = wave % WC;
+  const int fr = lane & 31, fg = lane >> 5;
+
+  f32x16 tot[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) tot[i][j][e] = 0.0f;
+  for (int q = 0; q < seg.n; ++q) {
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    accumulate_k<TM, TN, WR, WC, true>(u.A[li], u.B[li], u.ld, u.ld, M, N, m0, n0, seg.ks[q], seg.ke[q], la, lb, acc);
+    const float w = seg.w[q];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tot[i][j][e] = fmaf(w, acc[i][j][e], tot[i][j][e]);
+  }
+
+  // Epilogue: each wavefront stages its tile through its own slice of the (free) LDS, a band of
+  // rows at a time, so that a lane ends up with four consecutive columns of one row: 16-byte
+  // loads of the parameters and their accumulators, the Adagrad step, 16-byte stores, and the
+  // bf16 copy of the new weights (not of the bias row).
+  constexpr int WM = 32 * TM, WN = 32 * TN;
+  const int mw = m0 + wr * WM, nw = n0 + wc * WN;
+  constexpr int SPF = WN + 4;
+  constexpr int ROWS = (WR * WC * 32 * SPF * 4 <= (BM + BN) * PITCH * 2) ? 32 : 16;
+  static_assert(WR * WC * ROWS * SPF * 4 <= (BM + BN) * PITCH * 2, "epilogue staging exceeds the operand buffer");
+  float* stf = reinterpret_cast<float*>(lds) + wave * (ROWS * SPF);
+  constexpr int CPR = WN / 4;
+  constexpr int RPI = 64 / CPR;
+  const int rr = lane / CPR, cc = (lane % CPR) * 4;
+  float* P = u.p + u.w_off[li];
+  float* S = u.state + u.w_off[li];
+  bf16_t* Wb = u.wb[li];
+#pragma unroll
+  for (int pass = 0; pass < WM / ROWS; ++pass) {
+    if (pass) __syncthreads();
+    constexpr int EPP = ROWS / 2;               // fragment elements per pass
+    const int tile = pass * ROWS / 32, e0 = (pass * ROWS % 32) / 2;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < EPP; ++e)
+        stf[(8 * (e >> 2) + 4 * fg + (e & 3)) * SPF + j * 32 + fr] = tot[tile][j][e0 + e];
+    __syncthreads();
+#pragma unroll
+    for (int r0 = 0; r0 < ROWS; r0 += RPI) {
+      const int r = r0 + rr, m = mw + pass * ROWS + r, n = nw + cc;
+      if (m < M && n < N) {   // (N is a multiple of 8: the four columns are inside together)
+        const float4 g = *reinterpret_cast<const float4*>(stf + r * SPF + cc);
+        const int64_t idx = (int64_t)m * N + n;
+        const float4 p0 = *reinterpret_cast<const float4*>(P + idx);
+        float4 s1 = *reinterpret_cast<const float4*>(S + idx);
+        s1.x = fmaf(g.x, g.x, s1.x); s1.y = fmaf(g.y, g.y, s1.y);
+        s1.z = fmaf(g.z, g.z, s1.z); s1.w = fmaf(g.w, g.w, s1.w);
+        float4 p1;
+        p1.x = p0.x - u.lr * g.x / (sqrtf(s1.x) + u.eps);
+        p1.y = p0.y - u.lr * g.y / (sqrtf(s1.y) + u.eps);
+        p1.z = p0.z - u.lr * g.z / (sqrtf(s1.z) + u.eps);
+        p1.w = p0.w - u.lr * g.w / (sqrtf(s1.w) + u.eps);
+        *reinterpret_cast<float4*>(S + idx) = s1;
+        *reinterpret_cast<float4*>(P + idx) = p1;
+        if (m < M - 1)
+          *reinterpret_cast<uint2*>(Wb + idx) = make_uint2((uint32_t)f2bf(p1.x) | ((uint32_t)f2bf(p1.y) << 16),
+                                                           (uint32_t)f2bf(p1.z) | ((uint32_t)f2bf(p1.w) << 16));
       }
     }
   }
@@ -414,6 +524,34 @@ hipError_t launch_gemm(const GemmArgs& a, const ShardTab& tab, hipStream_t s) {
   else if (blocks(128, 128) >= MIN_BLOCKS) launch_bf16_variant<2, 2, 2, 2>(a, tab, groups, s);
   else if (blocks(128, 64) >= MIN_BLOCKS) launch_bf16_variant<2, 1, 2, 2>(a, tab, groups, s);
   else launch_bf16_variant<1, 1, 2, 2>(a, tab, groups, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_wgrad_update(const WgradUpdateArgs& a, const KSegments& seg, hipStream_t s) {
+  // The largest tile that still gives about two hundred blocks: every block walks the whole batch,
+  // so a large tile means few operand bytes per output but also few blocks, each pulling its
+  // operands at the rate of one compute unit.  (Config-2 model at 4096 samples, running beside the
+  // sparse update: 128 x 128 / 128 x 64 / 64 x 64 tiles = 102 / 204 / 396 blocks took 126 / 115 /
+  // 107 us, the step 256.1 / 255.0 / 254.8 us; alone 78 / 55 / 48 us.)
+  auto blocks_of = [&](int bm, int bn) {
+    int n = 0;
+    for (int l = 0; l < a.n_layers; ++l) n += ((a.M[l] + bm - 1) / bm) * ((a.N[l] + bn - 1) / bn);
+    return n;
+  };
+  const int tv = blocks_of(128, 128) >= 200 ? 0 : blocks_of(128, 64) >= 200 ? 1 : 2;
+  const int BM = tv == 2 ? 64 : 128, BN = tv == 0 ? 128 : 64;
+  WgradUpdateArgs u = a;
+  u.tile_base[0] = 0;
+  for (int l = 0; l < u.n_layers; ++l) {
+    if (u.M[l] <= 0 || u.N[l] <= 0 || (u.N[l] & 7)) return hipErrorInvalidValue;
+    u.tiles_n[l] = (u.N[l] + BN - 1) / BN;
+    u.tile_base[l + 1] = u.tile_base[l] + ((u.M[l] + BM - 1) / BM) * u.tiles_n[l];
+  }
+  const int blocks = u.tile_base[u.n_layers];
+  if (blocks <= 0) return hipSuccess;
+  if (tv == 0) hipLaunchKernelGGL((wgrad_update_kernel<2, 2, 2, 2>), dim3(blocks), dim3(256), 0, s, u, seg);
+  else if (tv == 1) hipLaunchKernelGGL((wgrad_update_kernel<2, 1, 2, 2>), dim3(blocks), dim3(256), 0, s, u, seg);
+  else hipLaunchKernelGGL((wgrad_update_kernel<1, 1, 2, 2>), dim3(blocks), dim3(256), 0, s, u, seg);
   return hipGetLastError();
 }
 
