@@ -411,6 +411,72 @@ def run_batch_sweep(args):
             "samples_per_s": [[bk, bk / (us * 1e-6)] for bk, us in curve]}
 
 
+def run_adjust_bs(args):
+    """ADJUST_BS on measured batch times (Section VI-A step 3, Eq. 2-3): the heterogeneous shards of
+    configuration 3 are stepped one worker at a time, every worker's batch processing time T_k is
+    measured with events (its weight gradients included), v_k = B_k / T_k goes into
+    antdt_assign_shard's speed mode, and the workers are timed again on the split that comes
+    back.  Reported: max_k T_k (what a bulk-synchronous iteration of K real workers would wait
+    for) before and after.  On one device all workers run on the same hardware, so what the
+    adjustment evens out here is the shard sizes; the batch time has a latency floor (see
+    --workload batch-sweep), which Eq. 3's linear model F(B) = B / v leaves out."""
+    import numpy as np
+    import torch
+
+    import paper_2404_09679_amd as A
+    import workload as wl
+
+    cfg = wl.CONFIGS[3]
+    dev = "cuda:0"
+    F, R, D = cfg.num_fields, cfg.rows_per_field, cfg.dim
+    tables = torch.empty((F * R, D), dtype=torch.float32, device=dev)
+    A.fill_tables(tables, F, R, D, 0.05)
+    state = torch.zeros((F * R, D), dtype=torch.float32, device=dev)
+    params = torch.from_numpy(wl.make_mlp_params(cfg)).to(dev)
+    pstate = torch.zeros_like(params)
+    b = wl.make_batch(cfg, 0)
+    ctx = A.Context(A.model_from_config(cfg, max_nnz=int(b.field_ptr[-1])))
+    ctx.bind(tables, state, params, pstate)
+    ctx.set_eager_weight_gradients(True)
+    ctx.set_batch(torch.from_numpy(b.ids).to(dev), b.field_ptr, torch.from_numpy(b.offsets).to(dev),
+                  torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.labels).to(dev))
+    K, B = cfg.num_shards, cfg.batch
+
+    def times(sizes):
+        ctx.assign_shard(B, K, sizes=sizes)
+        out = []
+        for k in range(K):
+            for _ in range(args.warmup):
+                ctx.worker_step(k)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.steps):
+                ctx.worker_step(k)
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) * 1e-3 / args.steps)
+        return out
+
+    before = list(cfg.shard_sizes)
+    t_before = times(before)
+    v = [n / t for n, t in zip(before, t_before)]
+    after = [n for _, n in ctx.assign_shard(B, K, speed=v)]
+    t_after = times(after)
+    equal = [n for _, n in ctx.assign_shard(B, K)]
+    t_equal = times(equal)
+    us = lambda ts: [round(t * 1e6, 1) for t in ts]
+    return {"metric": "slowest worker's batch processing time before and after ADJUST_BS", "unit": "us", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "data": "synthetic", "dtype": "bf16",
+            "config": {"workload": f"configs[2] {cfg.name}: worker_step of each of the {K} shards, one at a time"},
+            "value": max(t_after) * 1e6,
+            "before": {"sizes": before, "T_us": us(t_before), "max_T_us": max(t_before) * 1e6},
+            "measured_speed_samples_per_s": [round(x) for x in v],
+            "after_eq3": {"sizes": after, "T_us": us(t_after), "max_T_us": max(t_after) * 1e6,
+                          "predicted_max_T_us": max(n / x for n, x in zip(after, v)) * 1e6},
+            "equal_split": {"sizes": equal, "T_us": us(t_equal), "max_T_us": max(t_equal) * 1e6}}
+
+
 def run_straggler_sim(args):
     """Job completion times under the injection pattern of Section VII-A.2, from the batch times
     measured on this GPU: ten workers whose batch time is the affine fit of the measured
@@ -529,7 +595,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "batch-sweep", "copy-calibration", "straggler-sim"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "batch-sweep", "copy-calibration", "straggler-sim", "adjust-bs"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -537,6 +603,8 @@ def main():
                  "use --gpus 1")
     if args.workload == "straggler-sim":
         out = run_straggler_sim(args)
+    elif args.workload == "adjust-bs":
+        out = run_adjust_bs(args)
     elif args.workload == "copy-calibration":
         out = run_copy_calibration(args)
     elif args.workload == "batch-sweep":

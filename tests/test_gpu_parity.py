@@ -274,6 +274,67 @@ def test_new_split_after_a_batched_step():
     check_iteration(MID_BF, (640, 360), tol=TOLBF, bf16_gemm_oracle=True, prelude=batched_step_with_another_split)
 
 
+def _time_worker_steps(ctx, K, reps=5):
+    """Device time of worker_step(k) for every shard: the smallest of `reps` event-bracketed runs, seconds."""
+    out = []
+    for k in range(K):
+        best = float("inf")
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            ctx.worker_step(k)
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e-3)
+        out.append(best)
+    return out
+
+
+def test_adjust_bs_from_measured_worker_step_times():
+    """ADJUST_BS (Section VI-A step 3, Eq. 2-3) closed on the device: the batch processing time T_k
+    of every worker is measured (worker_step of its shard, weight gradients included), the
+    throughput v_k = B_k / T_k goes into antdt_assign_shard's speed mode, and the split that
+    comes back (i) keeps the global batch (constraint of Eq. 1), (ii) is optimal for Eq. 3 under
+    these measured speeds: its objective meets the continuous lower bound B / sum v within one
+    sample of the slowest worker, and on a reduced batch it equals the brute-force optimum
+    exactly, (iii) runs: the iteration on the new split matches the oracle."""
+    from fractions import Fraction
+    from gpu_helpers import GpuRun
+    from helpers import tables_as_f32
+    cfg = wl.scaled(wl.CONFIGS[3], name="cfg3-shape", rows_per_field=20_000,
+                    shard_sizes=(64, 96, 128, 192, 256, 320, 384, 512))
+    K, B = cfg.num_shards, cfg.batch
+    tables, state, flat, fstate, batch = make_inputs(cfg)
+    run = GpuRun(cfg, tables, flat, state, fstate, max_batch=B, max_shards=K, eager=True)
+    run.set_batch(batch)
+    run.ctx.assign_shard(B, K, sizes=cfg.shard_sizes)
+    for k in range(K):
+        run.ctx.worker_step(k)                       # warm
+    T = _time_worker_steps(run.ctx, K)
+    assert all(t > 0 for t in T)
+    v = [n / t for n, t in zip(cfg.shard_sizes, T)]
+    new = run.ctx.assign_shard(B, K, speed=v)
+    lens = [n for _, n in new]
+    assert sum(lens) == B and min(lens) >= 0 and [s for s, _ in new] == list(np.cumsum([0] + lens[:-1]))
+    z = max(Fraction(n) / Fraction(x) for n, x in zip(lens, v))
+    bound = Fraction(B) / sum(Fraction(x) for x in v)
+    assert bound <= z <= bound + 1 / Fraction(min(v))
+    small = run.ctx.assign_shard(24, 4, speed=v[:4])
+    best, _ = oracle.minmax_split_bruteforce(24, v[:4])
+    assert oracle.minmax_objective([n for _, n in small], v[:4]) == best
+    # the iteration on the new split
+    t32 = tables_as_f32(cfg, tables)
+    model, res, agg, upd = oracle_iteration(cfg, t32, state, flat, fstate, batch, lens, bf16_gemm=True)
+    run.iteration(lens, batched=False)
+    assert_close(run.g_dense, flat_dense_grad(cfg, agg.dW, agg.db), TOLBF, "aggregated dense gradient", BF16_MAX_TOL)
+    for f in range(cfg.num_fields):
+        u, so, ss, G = run.coalesced[f]
+        assert np.array_equal(u.astype(np.int64), agg.unique_ids[f]) and np.array_equal(so.astype(np.int64), agg.seg_offsets[f])
+        assert_close(G, agg.G[f], TOLBF, f"coalesced gradient, field {f}", BF16_MAX_TOL)
+    assert rel_err(run.params.cpu().numpy(), flat_layers(cfg, upd.layers))[0] <= TOLBF
+
+
 def test_gradient_accumulation_plan_as_micro_batch_shards():
     """Section VI-B: every device computes C_i micro-batches of B_i samples before the
     synchronisation.  The GPU runs the plan's micro-batches as shards; the oracle runs one
