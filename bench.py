@@ -140,6 +140,8 @@ def run_ranking(args, cfg_id):
     model = A.model_from_config(cfg, max_nnz=max_nnz)
     ctx = A.Context(model)
     ctx.bind(tables, state, params, pstate)
+    if args.single_stream:   # no overlap: every kernel on the launch stream (stand-alone durations per class)
+        ctx.set_library_streams(False)
     for i, b in enumerate(batches):   # fingerprints of the generated inputs, for the run log
         h = hashlib.sha256()
         for arr in (b.ids, b.offsets, b.dense, b.labels):
@@ -290,6 +292,7 @@ def run_ranking(args, cfg_id):
         "step_us": {"median": float(np.median(step_us)), "p10": float(np.percentile(step_us, 10)),
                     "p90": float(np.percentile(step_us, 90))},
         "kernel_us_per_step": breakdown,
+        "streams": "caller's stream only" if args.single_stream else "launch stream + 2 library streams",
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, batches[0])
@@ -597,6 +600,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "batch-sweep", "copy-calibration", "straggler-sim", "adjust-bs"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="ranking workloads: enqueue every kernel on one stream (per-kernel durations without overlap)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: the library runs on one GPU only (the K workers are shards on that device); "

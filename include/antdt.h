@@ -243,6 +243,17 @@ int antdt_apply_update(antdt_ctx* ctx, void* stream);
 int antdt_set_eager_weight_gradients(antdt_ctx* ctx, int32_t on);
 
 /*
+ * on == 0: every kernel of the following iterations is enqueued on the caller's stream, one
+ * after the other, although the context owns streams (the order a context bound by
+ * antdt_bind_static always uses: per-kernel durations without overlap, captures of a whole
+ * iteration on one stream).  on != 0 (the state after antdt_bind): the sort and run detection run
+ * on a stream of the library beside the MLP, the weight-gradient work on another beside the
+ * input-gradient product and the sparse update.  Results are the same.  To be called between
+ * iterations (ANTDT_BAD_STATE while work of an iteration is outstanding).  Host only.
+ */
+int antdt_set_library_streams(antdt_ctx* ctx, int32_t on);
+
+/*
  * Learning rate of the following antdt_apply_update calls (the ADJUST_LR global action of
  * Table II changes it between iterations; the optimizer state is kept).  lr finite, >= 0.
  * Host only.

@@ -24,7 +24,7 @@ EXPORTS = [
     "antdt_profile", "antdt_profile_read", "antdt_kernel_name",
     "antdt_plan_accumulation", "antdt_expand_accumulation", "antdt_set_lr", "antdt_validate_batch",
     "antdt_set_shard_scale", "antdt_stream_copy", "antdt_profile_overhead", "antdt_bind_static",
-    "antdt_set_eager_weight_gradients",
+    "antdt_set_eager_weight_gradients", "antdt_set_library_streams",
     "antdt_dds_create", "antdt_dds_destroy", "antdt_dds_num_shards", "antdt_dds_fetch", "antdt_dds_report_done",
     "antdt_dds_release_worker", "antdt_dds_shard", "antdt_dds_counts", "antdt_simulate_bsp",
 ]
@@ -97,6 +97,7 @@ def _load():
     lib.antdt_kernel_name.restype = C.c_char_p
     lib.antdt_set_lr.argtypes = [vp, f32]
     lib.antdt_set_eager_weight_gradients.argtypes = [vp, i32]
+    lib.antdt_set_library_streams.argtypes = [vp, i32]
     lib.antdt_set_shard_scale.argtypes = [vp, C.POINTER(C.c_double), i32]
     lib.antdt_stream_copy.argtypes = [vp, vp, i64, vp]
     lib.antdt_profile_overhead.argtypes = [vp, vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -263,6 +264,9 @@ class Context:
 
     def set_eager_weight_gradients(self, on: bool):
         self._check(lib.antdt_set_eager_weight_gradients(self._h, 1 if on else 0))
+
+    def set_library_streams(self, on: bool):
+        self._check(lib.antdt_set_library_streams(self._h, 1 if on else 0))
 
     def set_lr(self, lr: float):
         self._check(lib.antdt_set_lr(self._h, lr))

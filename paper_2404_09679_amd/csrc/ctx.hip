@@ -171,12 +171,13 @@ struct antdt_ctx {
   // bound by antdt_bind_static: the workspace is the library's static device buffer and every
   // kernel goes to the caller's stream (no library-owned stream or event exists or is created)
   bool static_bound = false;
+  bool no_streams = false;   // option: everything on the caller's stream although the library's streams exist
   int static_device = -1;
 };
 
 // The library's own streams, or none when the context works on the caller's stream only.
-static inline hipStream_t side_stream(const antdt_ctx* c) { return c->static_bound ? nullptr : c->side; }
-static inline hipStream_t wgrad_stream(const antdt_ctx* c) { return c->static_bound ? nullptr : c->wside; }
+static inline hipStream_t side_stream(const antdt_ctx* c) { return (c->static_bound || c->no_streams) ? nullptr : c->side; }
+static inline hipStream_t wgrad_stream(const antdt_ctx* c) { return (c->static_bound || c->no_streams) ? nullptr : c->wside; }
 
 static int fail(antdt_ctx* c, int code, const std::string& msg) {
   if (c) c->err = msg;
@@ -900,7 +901,7 @@ static int worker_range(antdt_ctx* c, int k0, int k1, float* loss_out, hipStream
   // at all: apply_update forms them inside the dense update (aggregated over the shards in
   // registers, never written per shard), and this step only records when their operands are
   // complete.  The per-shard gradients of the contract are computed when a view asks for them.
-  const bool deferred = c->act_bf16 && L > 1 && ws != s && !c->eager_wgrad;
+  const bool deferred = c->act_bf16 && L > 1 && c->wside && !c->static_bound && !c->eager_wgrad;
   c->wgrad_deferred = deferred;
   c->shard_grads_done = false;
   if (deferred && L == 2) HIP_TRY(c, hipEventRecord(c->ev_dh[0], s));  // dH_1 comes from the loss kernel
@@ -1063,6 +1064,16 @@ int antdt_set_eager_weight_gradients(antdt_ctx* c, int32_t on) {
   return ANTDT_OK;
 }
 
+int antdt_set_library_streams(antdt_ctx* c, int32_t on) {
+  if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_library_streams: null context");
+  bool stepped = false;
+  for (int k = 0; k < ANTDT_MAX_SHARDS; ++k) stepped = stepped || c->stepped[k];
+  if (c->side_pending || c->wgrad_pending || stepped)
+    return fail(c, ANTDT_BAD_STATE, "antdt_set_library_streams: call it between iterations (after antdt_apply_update or antdt_bind)");
+  c->no_streams = on == 0;
+  return ANTDT_OK;
+}
+
 int antdt_set_lr(antdt_ctx* c, float lr) {
   if (!c) return fail(nullptr, ANTDT_INVALID_ARG, "antdt_set_lr: null context");
   if (!(lr >= 0.f) || !isfinite(lr)) return fail(c, ANTDT_INVALID_ARG, "antdt_set_lr: lr must be finite and >= 0");
@@ -1095,7 +1106,12 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
     // Weight gradients, their aggregation over the shards and the dense update in one kernel
     // (the per-shard and the aggregated gradient stay in registers), behind the event that
     // says the worker step's activations and pre-activation gradients are complete.
-    HIP_TRY(c, hipStreamWaitEvent(ds, c->ev_dh[0], 0));
+    if (ds != s) {
+      HIP_TRY(c, hipStreamWaitEvent(ds, c->ev_dh[0], 0));
+    } else {  // (per-shard gradients that a view asked for may still be in flight on the library's stream)
+      const int rcj = join_wgrad(c, s);
+      if (rcj) return rcj;
+    }
     const int Lh = c->L - 1;  // hidden layers
     if (!c->shard_grads_done) {  // last layer: per-shard weight sums (its bias sum is already there)
       HeadReduceArgs r = c->head_reduce_args;
@@ -1150,8 +1166,10 @@ int antdt_apply_update(antdt_ctx* c, void* stream) {
       const int rc = transpose_weights(c, ds);  // the forward operand copies W_l^T from the new W_l
       if (rc) return rc;
     }
-    HIP_TRY(c, hipEventRecord(c->ev_wgrad, ds));
-    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_wgrad, 0));
+    if (ds != s) {
+      HIP_TRY(c, hipEventRecord(c->ev_wgrad, ds));
+      HIP_TRY(c, hipStreamWaitEvent(s, c->ev_wgrad, 0));
+    }
     c->wgrad_pending = false;  // `s` now waits for everything on that stream
   } else {
     DenseAdagradArgs a;

@@ -2,7 +2,10 @@
 
     python pmc_summary.py <dir>
     python pmc_summary.py --by-kernel <dir>     (any workload; no calibration runs needed:
-                                                                      FETCH_SIZE x 2, WRITE_SIZE x 1 as calibrated)
+                                                 FETCH_SIZE x 2, WRITE_SIZE x 1 as calibrated)
+    python pmc_summary.py --l1-latency <dir>    (<dir> = one rocprofv3 --pmc output with the vector-L1 counters
+                                                 TCP_TCC_READ_REQ_sum TCP_TCC_READ_REQ_LATENCY_sum
+                                                 TCP_PENDING_STALL_CYCLES_sum GRBM_GUI_ACTIVE)
 
 <dir> holds four rocprofv3 --pmc outputs (csv), one counter each:
     bench_FETCH_SIZE/ bench_WRITE_SIZE/   python3 bench.py --steps 40 --warmup 10 --no-cpu-baseline
@@ -45,6 +48,10 @@ def class_totals(rows):
             after_head, cls = True, "head"
         elif "head_reduce" in k:
             cls = "head_reduce"
+        elif "wgrad_update" in k:
+            cls = "wgrad_adagrad"
+        elif "transpose" in k:
+            cls = "transpose"
         elif "gemm_" in k:  # the grouped instantiations (last template argument true) are the weight gradients
             cls = "gemm_fwd" if not after_head else ("gemm_wgrad" if "true>" in k else "gemm_bwd")
         elif "seg_reduce" in k:
@@ -113,8 +120,31 @@ def by_kernel(d, fscale=2.0, wscale=1.0):
             print(f"{k[:72]:72s} {n:8d} {f / n:11.1f} {w / n:11.1f}")
 
 
+def l1_latency(d):
+    """Per kernel: vector-L1 read requests to L2 per launch and their mean latency in cycles, from a run with
+    --pmc TCP_TCC_READ_REQ_sum TCP_TCC_READ_REQ_LATENCY_sum TCP_PENDING_STALL_CYCLES_sum GRBM_GUI_ACTIVE."""
+    tot = collections.defaultdict(lambda: collections.defaultdict(float))
+    n = collections.defaultdict(int)
+    for r in _rows(d):
+        k = r["Kernel_Name"].replace("antdt::(anonymous namespace)::", "").replace("antdt::", "").replace("void ", "")
+        tot[k][r["Counter_Name"]] += float(r["Counter_Value"])
+        if r["Counter_Name"] == "TCP_TCC_READ_REQ_sum":
+            n[k] += 1
+    print(f"{'kernel':64s} {'launches':>8s} {'L1->L2 reads':>13s} {'mean latency':>13s} {'pending stall':>14s} {'active':>10s}   per launch")
+    for k, c in sorted(tot.items(), key=lambda kv: -kv[1].get("TCP_TCC_READ_REQ_sum", 0.0)):
+        if not n[k] or "at::native" in k or "fill_tables" in k:
+            continue
+        req = c.get("TCP_TCC_READ_REQ_sum", 0.0)
+        if req / n[k] < 1000:
+            continue
+        print(f"{k[:64]:64s} {n[k]:8d} {req / n[k]:13.0f} {c.get('TCP_TCC_READ_REQ_LATENCY_sum', 0.0) / max(req, 1):13.0f} "
+              f"{c.get('TCP_PENDING_STALL_CYCLES_sum', 0.0) / n[k]:14.0f} {c.get('GRBM_GUI_ACTIVE', 0.0) / n[k] / 8:10.0f}")
+
+
 if __name__ == "__main__":
     if sys.argv[1] == "--by-kernel":
         by_kernel(sys.argv[2])
+    elif sys.argv[1] == "--l1-latency":
+        l1_latency(sys.argv[2])
     else:
         main(sys.argv[1])

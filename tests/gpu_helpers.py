@@ -24,7 +24,7 @@ class GpuRun:
     """One model instance on the GPU with the tensors the library is bound to."""
 
     def __init__(self, cfg, tables_np, flat_params, state_np=None, flat_state=None, gemm_dtype=None,
-                 max_batch=None, max_nnz=None, max_shards=None, static=False, eager=False):
+                 max_batch=None, max_nnz=None, max_shards=None, static=False, eager=False, streams=True):
         self.cfg = cfg
         self.tables = upload_tables(cfg, tables_np)
         n_rows = cfg.num_fields * cfg.rows_per_field
@@ -39,6 +39,8 @@ class GpuRun:
         self.model = A.model_from_config(cfg, max_batch=max_batch, max_nnz=max_nnz, max_shards=max_shards,
                                          gemm_dtype=gemm_dtype)
         self.ctx = A.Context(self.model)
+        if not streams:   # every kernel on the caller's stream
+            self.ctx.set_library_streams(False)
         if eager:    # every worker step computes its own weight gradients
             self.ctx.set_eager_weight_gradients(True)
         if static:   # the library's static device buffer is the workspace (antdt_bind_static)

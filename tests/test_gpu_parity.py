@@ -670,6 +670,33 @@ def test_weight_gradients_in_the_worker_step_or_inside_the_dense_update():
     assert rel_err(run.params.cpu().numpy(), flat_layers(MID_BF, upd.layers))[0] <= TOLBF
 
 
+def test_single_stream_option_gives_the_same_results():
+    """antdt_set_library_streams(0): the same kernels in one stream; results equal bit for bit,
+    with views in between (per-shard gradients computed on request) and without."""
+    from gpu_helpers import GpuRun
+    cfg = MID_BF
+    tables, state, flat, fstate, batch = make_inputs(cfg, nonzero_state=True)
+    got = []
+    for streams in (True, False):
+        run = GpuRun(cfg, tables, flat, state, fstate, streams=streams)
+        run.set_batch(batch)
+        run.iteration(cfg.shard_sizes, batched=True)
+        run.set_batch(wl.make_batch(cfg, 1))
+        run.ctx.assign_shard(cfg.batch, len(cfg.shard_sizes), sizes=cfg.shard_sizes)
+        run.ctx.worker_step_all(run.loss)
+        run.ctx.aggregate()
+        run.ctx.apply_update()
+        torch.cuda.synchronize()
+        got.append((run.tables.cpu().numpy().copy(), run.params.cpu().numpy().copy(), run.pstate.cpu().numpy().copy(),
+                    run.g_dense.copy(), [s[1] for s in run.shard_out]))
+        with pytest.raises(Exception):
+            run.ctx.worker_step_all(run.loss)
+            run.ctx.set_library_streams(True)     # not in the middle of an iteration
+    for a, b in zip(got[0][:4], got[1][:4]):
+        assert np.array_equal(a, b)
+    assert all(np.array_equal(a, b) for a, b in zip(got[0][4], got[1][4]))
+
+
 def test_repeatable_bitwise():
     from gpu_helpers import GpuRun
     cfg = MID
