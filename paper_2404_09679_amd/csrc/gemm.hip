@@ -244,20 +244,25 @@ __global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, Sha
         constexpr int HV = 64 / CPI;
         const int col = lane % CPI, hv = lane / CPI;
         const int n = nw + col;
-        for (int mc = hv; mc < PM / 8; mc += HV) {
-          const int mb = mp + mc * 8;
-          if (n < p.N && mb < p.M) {
+        // Groups of eight rows that start where the destination (sample index ct_col0 + row) is a
+        // multiple of eight, so that a full group is one aligned 16-byte store whatever sample
+        // the shard starts at; the rows before the first such boundary and past the last row of
+        // the matrix go out element by element.
+        const int lead = (int)((8 - ((p.ct_col0 + mp) & 7)) & 7);  // rows before the first boundary
+        for (int mc = hv; mc <= PM / 8; mc += HV) {
+          const int r0 = lead + (mc - 1) * 8;                     // first staged row of the group (may be < 0)
+          if (n < p.N && r0 < PM && r0 + 8 > 0) {
             bf16_t h[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = st[(mc * 8 + e) * SP + col];
-            bf16_t* dst = p.CT + (int64_t)n * p.ldct + p.ct_col0 + mb;
-            if (mb + 7 < p.M && ((p.ct_col0 + mb) & 7) == 0) {
+            for (int e = 0; e < 8; ++e) h[e] = st[min(max(r0 + e, 0), PM - 1) * SP + col];
+            bf16_t* dst = p.CT + (int64_t)n * p.ldct + p.ct_col0 + mp + r0;
+            if (r0 >= 0 && r0 + 8 <= PM && mp + r0 + 7 < p.M) {
               *reinterpret_cast<uint4*>(dst) = make_uint4((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16),
                                                           (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16));
             } else {
 #pragma unroll
               for (int e = 0; e < 8; ++e)
-                if (mb + e < p.M) dst[e] = h[e];
+                if (r0 + e >= 0 && r0 + e < PM && mp + r0 + e < p.M) dst[e] = h[e];
             }
           }
         }
