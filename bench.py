@@ -30,14 +30,18 @@ VALU_FP32_PEAK_TFLOPS = 157.3  # fp32 vector arithmetic (the fp32 products of sm
 # aside) still has the fingerprint it had when the counters were taken.
 MEASURED_TRAFFIC = {
     "cfg2": {
-        "gemm_fwd": (73.7e6, "gemm.hip"), "gemm_bwd": (90.6e6, "gemm.hip"), "gemm_wgrad": (192.8e6, "gemm.hip"),
+        "gemm_fwd": (73.7e6, "gemm.hip"), "gemm_bwd": (90.6e6, "gemm.hip"), "wgrad_adagrad": (183.9e6, "gemm.hip"),
         "pool": (92.3e6, "embed.hip"),
-        "sparse_adagrad": (272.1e6, "coalesce.hip"), "seg_reduce_long": (1.5e6, "coalesce.hip"),
-        "dense_adagrad": (100.7e6, "optim.hip"),
+        "sparse_adagrad": (203.1e6, "coalesce.hip"), "seg_reduce_long": (1.5e6, "coalesce.hip"),
     },
-    "sha1": {"gemm.hip": "5de0dd76a699c9826bd9f2a88656383688aeca47",
+    "cfg3": {"sparse_adagrad": (743.5e6, "coalesce.hip"), "wgrad_adagrad": (623.9e6, "gemm.hip"),
+             "pool": (304.6e6, "embed.hip")},
+    "cfg4": {"sparse_adagrad": (8140.2e6, "coalesce.hip"), "wgrad_adagrad": (2044.1e6, "gemm.hip"),
+             "pool": (2247.6e6, "embed.hip")},
+    "cfg5": {"adam": (15032.4e6, "optim.hip")},
+    "sha1": {"gemm.hip": "6405cfc337e106d6118d10dd599b75f5bd701f3c",
              "embed.hip": "2ab400f86171f3c0a2539f685328e0b9611bdaef",
-             "coalesce.hip": "36661ca5f13ea0175ab0003d4c43bfd419091a96",
+             "coalesce.hip": "4b6a4dfe75df28619c9bbf532ce2c0c66dac19a7",
              "optim.hip": "79090e5f4d378e258fa3538b8574f6e9a57c6998"},
 }
 
@@ -599,7 +603,8 @@ def run_dense(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"configs[4] {dc.name}: {K} gradient buffers x 2^28 fp32, fused Adam"},
         "roofline": dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                         frac=achieved / HBM_PEAK_GBS, frac_of_measured_copy=achieved / copy_gbs, traffic=None,
+                         frac=achieved / HBM_PEAK_GBS, frac_of_measured_copy=achieved / copy_gbs,
+                         traffic=_measured_traffic("cfg5", "adam", 1.0) if (K, n) == (8, 1 << 28) else None,
                          kernel="adam", avg_launch_us=avg_ms * 1e3, algorithmic_per_launch=nbytes),
         "measured_copy_gbs": copy_gbs,
     }
