@@ -646,6 +646,19 @@ def test_training_model_follows_hand_worked_schedules(name, cfg, want):
     assert got == want
 
 
+def test_hash_finaliser_matches_the_published_murmurhash3_vectors():
+    """MurmurHash3 x86_32 of the empty input is its finaliser applied to the seed; the published
+    verification values for seeds 0, 1 and 0xffffffff are 0, 0x514E28B7 and 0x81F16F39.  The
+    finaliser drives both the injection pattern of the training model and the procedural table
+    values of the input generators."""
+    from oracle import dds_sim as D
+    vectors = {0x00000000: 0x00000000, 0x00000001: 0x514E28B7, 0xFFFFFFFF: 0x81F16F39}
+    for seed, want in vectors.items():
+        assert D.fmix32(seed) == want
+    got = wl.fmix32(np.array(list(vectors), dtype=np.uint32))
+    assert [int(v) for v in got] == list(vectors.values())
+
+
 def test_transient_pattern_is_deterministic_and_has_the_stated_rate():
     from oracle import dds_sim as D
     hits = sum(D.disturbed(7, w, i, 0.3) for w in range(400) for i in range(10))
