@@ -23,17 +23,35 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
   return lane == 0 ? 0ull : (~0ull >> (64 - lane));
 }
 
+// Block -> (field, tile) for the kernels that walk the lookups of the fields tile by tile.  The
+// hardware hands block i to XCD i mod 8, and every XCD has an L2 of its own: the blocks whose index
+// is x modulo 8 take the tiles of the fields x, x + 8, x + 16, ..., so that every pass over a
+// field's lookups runs on one XCD.  The scattered 4-byte stores of a sort pass are then assembled
+// into full lines in that L2 (spread over eight L2s, each wrote its partial lines back: 3.7 times
+// the payload), and the next pass over the field finds them there.
+__device__ __forceinline__ bool field_tile_of_block(const TileBase& tb, int F, int& f, int& t) {
+  int slot = blockIdx.x >> 3;
+  for (f = blockIdx.x & 7; f < F; f += 8) {
+    const int n = tb.t[f + 1] - tb.t[f];
+    if (slot < n) {
+      t = slot;
+      return true;
+    }
+    slot -= n;
+  }
+  return false;
+}
+
 // ----------------------------------------------------------------- sort
 // Histogram layout: hist[(tile_base[f] + tile) << rb | digit] (digits of a tile contiguous);
 // digit_base[f << rb | digit] = number of the field's keys with a smaller digit.
 
 // Digit histogram of one tile.
 __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const int32_t* keys, uint32_t* hist,
-                                                                 FieldPtr fp, TileBase tb, int shift, int rb) {
+                                                                 FieldPtr fp, TileBase tb, int F, int shift, int rb) {
   __shared__ uint32_t h[MAX_BINS];
-  const int f = blockIdx.y, t = blockIdx.x;
-  const int tiles = tb.t[f + 1] - tb.t[f];
-  if (t >= tiles) return;
+  int f, t;
+  if (!field_tile_of_block(tb, F, f, t)) return;
   const int nb = 1 << rb;
   const int64_t base = fp.p[f];
   const int nnz = (int)(fp.p[f + 1] - base);
@@ -101,15 +119,25 @@ __global__ __launch_bounds__(MAX_BINS) void sort_scan_kernel(uint32_t* hist, uin
 // ballot per digit bit, the per-wave running count of the digit lives in LDS.
 __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     const int32_t* keys_in, const int32_t* pay_in, int32_t* keys_out, int32_t* pay_out, const uint32_t* hist,
-    const uint32_t* digit_base, FieldPtr fp, TileBase tb, int shift, int rb) {
+    const uint32_t* digit_base, FieldPtr fp, TileBase tb, int F, int shift, int rb) {
   __shared__ uint32_t cnt[SORT_WAVES][MAX_BINS];
-  const int f = blockIdx.y, t = blockIdx.x;
-  const int tiles = tb.t[f + 1] - tb.t[f];
-  if (t >= tiles) return;
+  __shared__ uint32_t gbase[MAX_BINS];
+  int f, t;
+  if (!field_tile_of_block(tb, F, f, t)) return;
   const int nb = 1 << rb;
   const int64_t base = fp.p[f];
   const int nnz = (int)(fp.p[f + 1] - base);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  // first position of every digit's keys of this tile in the output (digits before it in the field +
+  // the digit's keys in earlier tiles): loaded up front with coalesced loads, looked up in LDS
+  const uint32_t* hb = hist + ((int64_t)(tb.t[f] + t) << rb);
+  const uint32_t* db = digit_base + ((int64_t)f << rb);
+  uint32_t gb[MAX_BINS / SORT_THREADS];
+#pragma unroll
+  for (int q = 0; q < MAX_BINS / SORT_THREADS; ++q) {
+    const int d = min((int)threadIdx.x + q * SORT_THREADS, nb - 1);
+    gb[q] = db[d] + hb[d];
+  }
   int32_t key[SORT_ITEMS], pay[SORT_ITEMS];
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {  // all loads first (clamped), so that they overlap
@@ -118,6 +146,9 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     pay[i] = pay_in[base + pos];
   }
   for (int d = threadIdx.x; d < SORT_WAVES * nb; d += SORT_THREADS) cnt[d >> rb][d & (nb - 1)] = 0;
+#pragma unroll
+  for (int q = 0; q < MAX_BINS / SORT_THREADS; ++q)
+    if ((int)threadIdx.x + q * SORT_THREADS < nb) gbase[threadIdx.x + q * SORT_THREADS] = gb[q];
   __syncthreads();
   const uint64_t lt = lanemask_lt();
   volatile uint32_t* cw = cnt[w];
@@ -151,13 +182,11 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     }
   }
   __syncthreads();
-  const uint32_t* hb = hist + ((int64_t)(tb.t[f] + t) << rb);
-  const uint32_t* db = digit_base + ((int64_t)f << rb);
   uint32_t dst[SORT_ITEMS];
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {
     const uint32_t d = ((uint32_t)key[i] >> shift) & (nb - 1);
-    dst[i] = db[d] + hb[d] + cnt[w][d] + rank[i];
+    dst[i] = gbase[d] + cnt[w][d] + rank[i];
   }
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {
@@ -223,8 +252,8 @@ __device__ __forceinline__ bool is_head(const int32_t* key, int pos) {
 // Number of run heads in each tile of the sorted keys.
 __global__ __launch_bounds__(SORT_THREADS) void seg_heads_kernel(SegArgs a, FieldPtr fp, TileBase tb) {
   __shared__ int wsum[SORT_WAVES];
-  const int f = blockIdx.y, t = blockIdx.x;
-  if (t >= tb.t[f + 1] - tb.t[f]) return;
+  int f, t;
+  if (!field_tile_of_block(tb, a.F, f, t)) return;
   const int32_t* key = a.key + fp.p[f];
   const int nnz = (int)(fp.p[f + 1] - fp.p[f]);
   int c = 0;
@@ -291,8 +320,8 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(SegArgs a, FieldPtr fp, 
 // Unique ids and segment offsets.  Thread j of a tile owns 8 consecutive sorted positions.
 __global__ __launch_bounds__(SORT_THREADS) void seg_emit_kernel(SegArgs a, FieldPtr fp, TileBase tb) {
   __shared__ int wsum[SORT_WAVES];
-  const int f = blockIdx.y, t = blockIdx.x;
-  if (t >= tb.t[f + 1] - tb.t[f]) return;
+  int f, t;
+  if (!field_tile_of_block(tb, a.F, f, t)) return;
   const int32_t* key = a.key + fp.p[f];
   const int nnz = (int)(fp.p[f + 1] - fp.p[f]);
   const int p0 = t * SORT_TILE + threadIdx.x * SORT_ITEMS;
@@ -714,16 +743,28 @@ void launch_reduce_variant(const SegArgs& a, unsigned blocks, unsigned finish_bl
 
 }  // namespace
 
+// Blocks of a launch whose block b works on tile (b / 8) of the fields b mod 8, b mod 8 + 8, ...:
+// eight times the largest number of tiles any of the eight groups of fields has.
+static unsigned tile_grid(const TileBase& tb, int F) {
+  int most = 0;
+  for (int x = 0; x < 8; ++x) {
+    int n = 0;
+    for (int f = x; f < F; f += 8) n += tb.t[f + 1] - tb.t[f];
+    most = std::max(most, n);
+  }
+  return (unsigned)(8 * std::max(most, 1));
+}
+
 hipError_t launch_sort_pass(const SortPlan& pl, const SortBuffers& sb, int pass, const FieldPtr& fp,
                             const TileBase& tb, Profiler* prof, hipStream_t s) {
   if (pl.total_tiles == 0) return hipSuccess;
   const int shift = pass * pl.radix_bits;
   const int32_t* kin = pass == 0 ? sb.ids : sb.key[(pass - 1) & 1];
   const int32_t* pin = pass == 0 ? sb.pay0 : sb.pay[(pass - 1) & 1];
-  dim3 grid(pl.max_tiles, pl.F);
+  dim3 grid(tile_grid(tb, pl.F));
   {
     ProfScope ps(prof, KID_SORT_HIST, s);
-    hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(SORT_THREADS), 0, s, kin, sb.hist, fp, tb, shift, pl.radix_bits);
+    hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(SORT_THREADS), 0, s, kin, sb.hist, fp, tb, pl.F, shift, pl.radix_bits);
   }
   {
     ProfScope ps(prof, KID_SORT_SCAN, s);
@@ -732,14 +773,14 @@ hipError_t launch_sort_pass(const SortPlan& pl, const SortBuffers& sb, int pass,
   {
     ProfScope ps(prof, KID_SORT_SCATTER, s);
     hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(SORT_THREADS), 0, s, kin, pin, sb.key[pass & 1],
-                       sb.pay[pass & 1], sb.hist, sb.digit_base, fp, tb, shift, pl.radix_bits);
+                       sb.pay[pass & 1], sb.hist, sb.digit_base, fp, tb, pl.F, shift, pl.radix_bits);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_segments(const SegArgs& a, const FieldPtr& fp, const TileBase& tb, const ShardTab& tab,
                            Profiler* prof, hipStream_t s) {
-  dim3 grid(a.max_tiles, a.F);
+  dim3 grid(tile_grid(tb, a.F));
   if (a.total_tiles > 0) {
     ProfScope ps(prof, KID_SEG_HEADS, s);
     hipLaunchKernelGGL(seg_heads_kernel, grid, dim3(SORT_THREADS), 0, s, a, fp, tb);
