@@ -172,28 +172,86 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     }
   }
   __syncthreads();
-  for (int d = threadIdx.x; d < nb; d += SORT_THREADS) {
-    uint32_t run = 0;
+  // Per digit: the counts of the wavefronts become exclusive prefixes (keys of the digit in
+  // earlier wavefronts of the tile), their sum the tile's count of the digit; an exclusive scan of
+  // these counts in digit order gives every key its place in the tile sorted by digit.
+  constexpr int DPT = MAX_BINS / SORT_THREADS;  // digits per thread: d = threadIdx.x + q * SORT_THREADS
+  __shared__ uint32_t dpre[MAX_BINS];
+  __shared__ uint32_t wsum[DPT][SORT_WAVES];
+  uint32_t tot[DPT], incl[DPT];
 #pragma unroll
-    for (int ww = 0; ww < SORT_WAVES; ++ww) {
-      const uint32_t c = cnt[ww][d];
-      cnt[ww][d] = run;
-      run += c;
+  for (int q = 0; q < DPT; ++q) {
+    const int d = threadIdx.x + q * SORT_THREADS;
+    uint32_t run = 0;
+    if (d < nb) {
+#pragma unroll
+      for (int ww = 0; ww < SORT_WAVES; ++ww) {
+        const uint32_t c = cnt[ww][d];
+        cnt[ww][d] = run;
+        run += c;
+      }
+    }
+    tot[q] = run;
+    incl[q] = run;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t v = __shfl_up(incl[q], o, 64);
+      if (lane >= o) incl[q] += v;
+    }
+    if (lane == 63) wsum[q][w] = incl[q];
+  }
+  __syncthreads();
+  {
+    uint32_t before = 0;  // keys of the tile with a digit handled by an earlier (q, wavefront)
+#pragma unroll
+    for (int q = 0; q < DPT; ++q) {
+      uint32_t mine = before;
+      for (int ww = 0; ww < SORT_WAVES; ++ww) {
+        if (ww < w) mine += wsum[q][ww];
+        before += wsum[q][ww];
+      }
+      const int d = threadIdx.x + q * SORT_THREADS;
+      if (d < nb) {
+        const uint32_t first = mine + incl[q] - tot[q];  // place of the digit's first key in the sorted tile
+        dpre[d] = first;
+        gbase[d] -= first;   // output position = gbase[d] + place in the sorted tile
+      }
     }
   }
   __syncthreads();
-  uint32_t dst[SORT_ITEMS];
+  uint32_t lp[SORT_ITEMS];
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {
     const uint32_t d = ((uint32_t)key[i] >> shift) & (nb - 1);
-    dst[i] = gbase[d] + cnt[w][d] + rank[i];
+    lp[i] = dpre[d] + cnt[w][d] + rank[i];
   }
+  __syncthreads();  // the counters are dead: their memory stages the tile sorted by digit
+  int32_t* skey = reinterpret_cast<int32_t*>(&cnt[0][0]);
+  int32_t* spay = skey + SORT_TILE;
+  static_assert(2 * SORT_TILE <= SORT_WAVES * MAX_BINS, "the staged tile must fit the counters' memory");
+  const int tile_count = min(SORT_TILE, nnz - t * SORT_TILE);
 #pragma unroll
   for (int i = 0; i < SORT_ITEMS; ++i) {
     const int pos = t * SORT_TILE + w * (64 * SORT_ITEMS) + i * 64 + lane;
-    if (pos < nnz && dst[i] < (uint32_t)nnz) {
-      keys_out[base + dst[i]] = key[i];
-      pay_out[base + dst[i]] = pay[i];
+    if (pos < nnz && lp[i] < (uint32_t)SORT_TILE) {
+      skey[lp[i]] = key[i];
+      spay[lp[i]] = pay[i];
+    }
+  }
+  __syncthreads();
+  // Consecutive threads hold consecutive keys of the sorted tile: keys of one digit go to consecutive
+  // positions of the output, so that their 4-byte stores merge into one request per run.
+#pragma unroll
+  for (int q = 0; q < SORT_ITEMS; ++q) {
+    const int j = q * SORT_THREADS + threadIdx.x;
+    if (j < tile_count) {
+      const int32_t k = skey[j];
+      const uint32_t d = ((uint32_t)k >> shift) & (nb - 1);
+      const uint32_t dst = gbase[d] + (uint32_t)j;
+      if (dst < (uint32_t)nnz) {
+        keys_out[base + dst] = k;
+        pay_out[base + dst] = spay[j];
+      }
     }
   }
 }
