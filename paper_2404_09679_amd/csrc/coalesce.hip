@@ -30,16 +30,16 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
 // into full lines in that L2 (spread over eight L2s, each wrote its partial lines back: 3.7 times
 // the payload), and the next pass over the field finds them there.
 __device__ __forceinline__ bool field_tile_of_block(const TileBase& tb, int F, int& f, int& t) {
-  int slot = blockIdx.x >> 3;
-  for (f = blockIdx.x & 7; f < F; f += 8) {
-    const int n = tb.t[f + 1] - tb.t[f];
-    if (slot < n) {
-      t = slot;
-      return true;
-    }
-    slot -= n;
-  }
-  return false;
+  constexpr int G = ANTDT_MAX_FIELDS / 8;
+  const int x = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int32_t* cum = tb.xcum[x];  // (one row of the table: a single scalar load)
+  if (slot >= cum[G]) return false;
+  int j = 0;
+#pragma unroll
+  for (int i = 1; i < G; ++i) j += slot >= cum[i] ? 1 : 0;
+  f = x + 8 * j;
+  t = slot - cum[j];
+  return f < F;
 }
 
 // ----------------------------------------------------------------- sort
@@ -804,13 +804,10 @@ void launch_reduce_variant(const SegArgs& a, unsigned blocks, unsigned finish_bl
 // Blocks of a launch whose block b works on tile (b / 8) of the fields b mod 8, b mod 8 + 8, ...:
 // eight times the largest number of tiles any of the eight groups of fields has.
 static unsigned tile_grid(const TileBase& tb, int F) {
-  int most = 0;
-  for (int x = 0; x < 8; ++x) {
-    int n = 0;
-    for (int f = x; f < F; f += 8) n += tb.t[f + 1] - tb.t[f];
-    most = std::max(most, n);
-  }
-  return (unsigned)(8 * std::max(most, 1));
+  int most = 1;
+  for (int x = 0; x < 8; ++x) most = std::max(most, (int)tb.xcum[x][ANTDT_MAX_FIELDS / 8]);
+  (void)F;
+  return (unsigned)(8 * most);
 }
 
 hipError_t launch_sort_pass(const SortPlan& pl, const SortBuffers& sb, int pass, const FieldPtr& fp,

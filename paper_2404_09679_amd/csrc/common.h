@@ -43,7 +43,11 @@ struct ShardTab {
 };
 struct TileBase {
   int32_t t[ANTDT_MAX_FIELDS + 1];  // prefix sum of sort tiles per field
+  // xcum[x][j] = tiles of the fields x, x + 8, ..., x + 8 (j - 1): the blocks with index x modulo 8 take the
+  // tiles of these fields in this order (16 fields per group at most; entries past the last field repeat the total)
+  int32_t xcum[8][ANTDT_MAX_FIELDS / 8 + 1];
 };
+static_assert(ANTDT_MAX_FIELDS % 8 == 0, "fields are dealt to eight groups");
 
 // Kernel classes for the optional event timing.
 enum KernelId {

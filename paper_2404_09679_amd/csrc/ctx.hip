@@ -544,6 +544,11 @@ static void plan_tiles(int F, const FieldPtr& fp, TileBase& tb, int& max_tiles, 
   }
   for (int f = F + 1; f <= ANTDT_MAX_FIELDS; ++f) tb.t[f] = tb.t[F];
   total_tiles = tb.t[F];
+  for (int x = 0; x < 8; ++x)
+    for (int j = 0; j < ANTDT_MAX_FIELDS / 8; ++j) {
+      const int f = x + 8 * j;
+      tb.xcum[x][j + 1] = tb.xcum[x][j] + (f < F ? tb.t[f + 1] - tb.t[f] : 0);
+    }
 }
 
 static void coalesce_whole_batch(antdt_ctx* c) {
