@@ -41,9 +41,9 @@ MEASURED_TRAFFIC = {
     "cfg5": {"adam": (15032.4e6, "optim.hip")},
     "sha1": {"gemm.hip": "6405cfc337e106d6118d10dd599b75f5bd701f3c",
              "embed.hip": "2ab400f86171f3c0a2539f685328e0b9611bdaef",
-             "coalesce.hip": "59bbd9a93acd432ae5dd22058d20a90fa2bd4060",
+             "coalesce.hip": "8a4a78e09c650e5d2236533d4402e370a2663b43",
              "optim.hip": "79090e5f4d378e258fa3538b8574f6e9a57c6998",
-             "ctx.hip": "20765aae76be5bdf04076642d7871d6ef44f3c3d"},
+             "ctx.hip": "61eb7572c3832fd95dcb74b7e9b648c38227aa35"},
 }
 
 
