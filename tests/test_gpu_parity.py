@@ -610,6 +610,14 @@ def test_mid_bf16_gemm_against_bf16_operand_oracle_and_plain_oracle():
     check_against_plain_oracle(MID_BF)
 
 
+@pytest.mark.parametrize("batch_index", [1, 2, 3])
+def test_other_batches_of_the_mid_size_models(batch_index):
+    """Other draws of the inputs (other run-length mixes for the sort, the block-per-chunk sums and
+    the lane-group sums), batched launch, both precisions."""
+    check_iteration(MID, MID.shard_sizes, nonzero_state=True, batched=True, batch_index=batch_index)
+    check_iteration(MID_BF, MID_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True, batched=True, batch_index=batch_index)
+
+
 def test_wide_hidden_layer_ragged_batch():
     check_iteration(WIDE_HIDDEN, WIDE_HIDDEN.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True, batched=True)
 
