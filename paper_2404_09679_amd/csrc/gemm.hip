@@ -315,7 +315,10 @@ __global__ __launch_bounds__(64 * WR * WC) void gemm_bf16_kernel(GemmArgs p, Sha
 // the sample ranges are formed one after the other, each from zero, and added up with their
 // weights in range order: g = fma(w_k, sum_k, g), the order in which the stand-alone dense
 // update adds the shards' gradients.
-template <int TM, int TN, int WR, int WC>
+// ONE: a single sample range (all shards of one weight, one after the other): its sum is scaled in
+// place, fma(w, sum, 0) = w * sum, and the second set of accumulators is not needed (fewer registers:
+// three wavefronts per SIMD instead of two, which leaves more room for the kernels running beside it).
+template <int TM, int TN, int WR, int WC, bool ONE>
 __global__ __launch_bounds__(64 * WR * WC) void wgrad_update_kernel(WgradUpdateArgs u, KSegments seg) {
   constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
   __shared__ __attribute__((aligned(16))) bf16_t lds[(BM + BN) * PITCH];
@@ -337,22 +340,33 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_update_kernel(WgradUpdateA
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) tot[i][j][e] = 0.0f;
-  for (int q = 0; q < seg.n; ++q) {
-    f32x16 acc[TM][TN];
+  if (ONE) {
+    accumulate_k<TM, TN, WR, WC, true>(u.A[li], u.B[li], u.ld, u.ld, M, N, m0, n0, seg.ks[0], seg.ke[0], la, lb, tot);
+    const float w = seg.w[0];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-    accumulate_k<TM, TN, WR, WC, true>(u.A[li], u.B[li], u.ld, u.ld, M, N, m0, n0, seg.ks[q], seg.ke[q], la, lb, acc);
-    const float w = seg.w[q];
+        for (int e = 0; e < 16; ++e) tot[i][j][e] = fmaf(w, tot[i][j][e], 0.0f);
+  } else {
+    for (int q = 0; q < seg.n; ++q) {
+      f32x16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) tot[i][j][e] = fmaf(w, acc[i][j][e], tot[i][j][e]);
+          for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+      accumulate_k<TM, TN, WR, WC, true>(u.A[li], u.B[li], u.ld, u.ld, M, N, m0, n0, seg.ks[q], seg.ke[q], la, lb, acc);
+      const float w = seg.w[q];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) tot[i][j][e] = fmaf(w, acc[i][j][e], tot[i][j][e]);
+    }
   }
 
   // Epilogue: each wavefront stages its tile through its own slice of the (free) LDS, a band of
@@ -554,9 +568,13 @@ hipError_t launch_wgrad_update(const WgradUpdateArgs& a, const KSegments& seg, h
   }
   const int blocks = u.tile_base[u.n_layers];
   if (blocks <= 0) return hipSuccess;
-  if (tv == 0) hipLaunchKernelGGL((wgrad_update_kernel<2, 2, 2, 2>), dim3(blocks), dim3(256), 0, s, u, seg);
-  else if (tv == 1) hipLaunchKernelGGL((wgrad_update_kernel<2, 1, 2, 2>), dim3(blocks), dim3(256), 0, s, u, seg);
-  else hipLaunchKernelGGL((wgrad_update_kernel<1, 1, 2, 2>), dim3(blocks), dim3(256), 0, s, u, seg);
+  const bool one = seg.n == 1;
+  if (tv == 0 && one) hipLaunchKernelGGL((wgrad_update_kernel<2, 2, 2, 2, true>), dim3(blocks), dim3(256), 0, s, u, seg);
+  else if (tv == 0) hipLaunchKernelGGL((wgrad_update_kernel<2, 2, 2, 2, false>), dim3(blocks), dim3(256), 0, s, u, seg);
+  else if (tv == 1 && one) hipLaunchKernelGGL((wgrad_update_kernel<2, 1, 2, 2, true>), dim3(blocks), dim3(256), 0, s, u, seg);
+  else if (tv == 1) hipLaunchKernelGGL((wgrad_update_kernel<2, 1, 2, 2, false>), dim3(blocks), dim3(256), 0, s, u, seg);
+  else if (one) hipLaunchKernelGGL((wgrad_update_kernel<1, 1, 2, 2, true>), dim3(blocks), dim3(256), 0, s, u, seg);
+  else hipLaunchKernelGGL((wgrad_update_kernel<1, 1, 2, 2, false>), dim3(blocks), dim3(256), 0, s, u, seg);
   return hipGetLastError();
 }
 
