@@ -36,10 +36,10 @@ MEASURED_TRAFFIC = {
     },
     "cfg3": {"sparse_adagrad": (753.6e6, "coalesce.hip"), "wgrad_adagrad": (623.8e6, "gemm.hip"),
              "pool": (304.6e6, "embed.hip")},
-    "cfg4": {"sparse_adagrad": (8413.1e6, "coalesce.hip"), "wgrad_adagrad": (2044.3e6, "gemm.hip"),
+    "cfg4": {"sparse_adagrad": (8411.5e6, "coalesce.hip"), "wgrad_adagrad": (2131.3e6, "gemm.hip"),
              "pool": (2245.4e6, "embed.hip")},
     "cfg5": {"adam": (15032.4e6, "optim.hip")},
-    "sha1": {"gemm.hip": "6405cfc337e106d6118d10dd599b75f5bd701f3c",
+    "sha1": {"gemm.hip": "67876aa8387e26f2bce5efd17e6ee8c9737eade0",
              "embed.hip": "2ab400f86171f3c0a2539f685328e0b9611bdaef",
              "coalesce.hip": "8a4a78e09c650e5d2236533d4402e370a2663b43",
              "optim.hip": "79090e5f4d378e258fa3538b8574f6e9a57c6998",
