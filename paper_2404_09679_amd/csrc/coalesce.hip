@@ -727,11 +727,23 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(SegArgs a, int chunk_bl
     slot = bid;
     nslots = nblk;
   }
-  for (int64_t u = lo + slot * groups_per_block + g; u < hi; u += nslots * groups_per_block) {
-    const int b = a.segabs[u], e = a.segabs[u + 1];
+  // The kernel is bound by the chain of dependent accesses of a run (its description -> its row,
+  // accumulators and sample indices -> the pooled-gradient rows of its samples), every wavefront
+  // slot of the device being taken: the bounds, field and row id of a run are requested together,
+  // and those of the group's next run while the current one is summed.
+  const int64_t ustep = nslots * groups_per_block;
+  int64_t u = lo + slot * groups_per_block + g;
+  int nb = 0, ne = 0, nf = 0, nid = 0;
+  if (u < hi) {
+    nb = a.segabs[u]; ne = a.segabs[u + 1]; nf = a.ufield[u]; nid = a.uniq[u];
+  }
+  for (; u < hi; u += ustep) {
+    const int b = nb, e = ne, f = nf, id = nid;
+    if (u + ustep < hi) {
+      nb = a.segabs[u + ustep]; ne = a.segabs[u + ustep + 1]; nf = a.ufield[u + ustep]; nid = a.uniq[u + ustep];
+    }
     if (e - b > a.long_threshold) continue;
-    const int f = a.ufield[u];
-    const int64_t row = (int64_t)f * a.R + min(max(a.uniq[u], 0), (int)(a.R - 1));
+    const int64_t row = (int64_t)f * a.R + min(max(id, 0), (int)(a.R - 1));
     float p0[4] = {0.f, 0.f, 0.f, 0.f};
     float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f);
     float srow0 = 0.f;
