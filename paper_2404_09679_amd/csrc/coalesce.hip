@@ -579,16 +579,23 @@ __device__ __forceinline__ float lookup_weight(const SegArgs& a, const int32_t* 
 }
 
 // g += w(lookup) * dX[sample, field slice] over sorted entries [b, e) of field f taken with
-// stride `step`, NF entries in flight (added in order).
+// stride `step`, NF entries in flight (added in order).  The sample indices of the next NF entries
+// are requested before the pooled-gradient rows of the current ones are waited for: the chain of
+// dependent accesses is one round trip per NF entries instead of two.
 template <bool MEAN, int NF = 4>
 __device__ __forceinline__ void accumulate_run(const SegArgs& a, int f, int c, int b, int e, int step, Row4& g) {
   const float* dxcol = a.dx + f * a.D + c * 4;
   const int32_t* off = MEAN ? a.offsets + (int64_t)f * (a.B + 1) : nullptr;
   int i = b;
+  int sn[NF];
+#pragma unroll
+  for (int q = 0; q < NF; ++q) sn[q] = i + q * step < e ? a.pay[i + q * step] : 0;
   for (; i + (NF - 1) * step < e; i += NF * step) {
     int s[NF];
 #pragma unroll
-    for (int q = 0; q < NF; ++q) s[q] = min(max(a.pay[i + q * step], 0), a.B - 1);
+    for (int q = 0; q < NF; ++q) s[q] = min(max(sn[q], 0), a.B - 1);
+#pragma unroll
+    for (int q = 0; q < NF; ++q) sn[q] = i + (NF + q) * step < e ? a.pay[i + (NF + q) * step] : 0;
     float w[NF];
     float4 x[NF];
 #pragma unroll
@@ -604,14 +611,28 @@ __device__ __forceinline__ void accumulate_run(const SegArgs& a, int f, int c, i
       g.v[3] = fmaf(w[q], x[q].w, g.v[3]);
     }
   }
-  for (; i < e; i += step) {
-    const int s = min(max(a.pay[i], 0), a.B - 1);
-    const float w = lookup_weight<MEAN>(a, off, s);
-    const float4 x = *reinterpret_cast<const float4*>(dxcol + (int64_t)s * a.lddx);
-    g.v[0] = fmaf(w, x.x, g.v[0]);
-    g.v[1] = fmaf(w, x.y, g.v[1]);
-    g.v[2] = fmaf(w, x.z, g.v[2]);
-    g.v[3] = fmaf(w, x.w, g.v[3]);
+  // fewer than NF entries are left; their sample indices are in sn[]
+  {
+    float w[NF];
+    float4 x[NF];
+#pragma unroll
+    for (int q = 0; q < NF; ++q) {
+      const int s = min(max(sn[q], 0), a.B - 1);
+      w[q] = 0.0f;
+      x[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i + q * step < e) {
+        w[q] = lookup_weight<MEAN>(a, off, s);
+        x[q] = *reinterpret_cast<const float4*>(dxcol + (int64_t)s * a.lddx);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < NF; ++q)
+      if (i + q * step < e) {
+        g.v[0] = fmaf(w[q], x[q].x, g.v[0]);
+        g.v[1] = fmaf(w[q], x[q].y, g.v[1]);
+        g.v[2] = fmaf(w[q], x[q].z, g.v[2]);
+        g.v[3] = fmaf(w[q], x[q].w, g.v[3]);
+      }
   }
 }
 
