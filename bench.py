@@ -32,16 +32,16 @@ MEASURED_TRAFFIC = {
     "cfg2": {
         "gemm_fwd": (73.7e6, "gemm.hip"), "gemm_bwd": (90.6e6, "gemm.hip"), "wgrad_adagrad": (183.9e6, "gemm.hip"),
         "pool": (92.3e6, "embed.hip"),
-        "sparse_adagrad": (201.1e6, "coalesce.hip"), "seg_reduce_long": (2.5e6, "coalesce.hip"),
+        "sparse_adagrad": (201.5e6, "coalesce.hip"), "seg_reduce_long": (2.5e6, "coalesce.hip"),
     },
-    "cfg3": {"sparse_adagrad": (753.6e6, "coalesce.hip"), "wgrad_adagrad": (623.8e6, "gemm.hip"),
+    "cfg3": {"sparse_adagrad": (761.0e6, "coalesce.hip"), "wgrad_adagrad": (623.8e6, "gemm.hip"),
              "pool": (304.6e6, "embed.hip")},
-    "cfg4": {"sparse_adagrad": (8411.5e6, "coalesce.hip"), "wgrad_adagrad": (2131.3e6, "gemm.hip"),
+    "cfg4": {"sparse_adagrad": (8871.4e6, "coalesce.hip"), "wgrad_adagrad": (2131.3e6, "gemm.hip"),
              "pool": (2245.4e6, "embed.hip")},
     "cfg5": {"adam": (15032.4e6, "optim.hip")},
     "sha1": {"gemm.hip": "67876aa8387e26f2bce5efd17e6ee8c9737eade0",
              "embed.hip": "2ab400f86171f3c0a2539f685328e0b9611bdaef",
-             "coalesce.hip": "8a4a78e09c650e5d2236533d4402e370a2663b43",
+             "coalesce.hip": "662ffdbbe53e42ee464a9896528c53d71366ee53",
              "optim.hip": "79090e5f4d378e258fa3538b8574f6e9a57c6998",
              "ctx.hip": "61eb7572c3832fd95dcb74b7e9b648c38227aa35"},
 }
