@@ -618,6 +618,18 @@ def test_other_batches_of_the_mid_size_models(batch_index):
     check_iteration(MID_BF, MID_BF.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True, batched=True, batch_index=batch_index)
 
 
+@pytest.mark.parametrize("batch", [512, 513, 1024, 1535])
+def test_lookup_counts_at_the_sort_tile_boundaries(batch):
+    """Every bag has four lookups: a field has exactly 2048 or 4096 lookups (whole sort tiles), or a
+    few more or fewer (a last tile with a handful of keys, or short of a handful); 9 fields, so the
+    groups of fields dealt to the eight XCDs differ in size."""
+    cfg = wl.RankingConfig(f"tile-boundary-{batch}", 9, 3000, 8, "f32", "elementwise", 2, (74, 16, 1), "f32",
+                           4, 1.1, (batch - 200, 200), wl.SEED0 + 300 + batch, min_bag=4)
+    b = wl.make_batch(cfg)
+    assert all(len(b.field_ids(f)) == 4 * batch for f in range(cfg.num_fields))
+    check_iteration(cfg, cfg.shard_sizes, batched=True, nonzero_state=True)
+
+
 def test_wide_hidden_layer_ragged_batch():
     check_iteration(WIDE_HIDDEN, WIDE_HIDDEN.shard_sizes, tol=TOLBF, bf16_gemm_oracle=True, batched=True)
 
